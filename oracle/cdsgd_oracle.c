@@ -1,0 +1,163 @@
+/*
+ * CD-SGD hot-path oracle -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+ *
+ * A plain, slow, scalar CPU statement of what one iteration of CD-SGD's
+ * formal-training loop computes on the data-parallel path: 2-bit threshold
+ * quantisation with an error-feedback residual, packing of the codes,
+ * decode-and-sum over N workers, and the two weight updates.  It exists so
+ * that the HIP library can be checked against something written directly from
+ * the paper.  It shares no code with the HIP path, is never called by it, and
+ * may be imported only by tests, the smoke check and the benchmark's
+ * cpu-baseline leg.
+ *
+ * One element at a time, one worker at a time, fp32 with round-to-nearest-even
+ * (the paper trains in fp32), no blocking, no SIMD intrinsics, no reordering.
+ * Build: gcc -O2 -fno-fast-math -ffp-contract=off (so that no multiply-add is
+ * fused behind our back and denormals are kept).
+ *
+ * Where each function comes from:
+ *   oracle_quantize      Sec. 2.3 (residual buffer of BIT-SGD) and Sec. 3.4.1
+ *                        (values beyond the threshold are sent as the threshold,
+ *                        the error is kept and re-offered later)
+ *   oracle_pack/unpack   Sec. 3.2.2 (32-bit gradients encoded into 2 bits and
+ *                        written to sml_buf); the bit layout is this build's
+ *                        convention, the paper gives none
+ *   oracle_decode_sum    Sec. 3.2.1 (server decodes to 32 bits before updating)
+ *                        and the sum in eq. 10
+ *   oracle_full_sum      the sum in eq. 1 / Alg. 1 correction branch
+ *   oracle_update        eq. 10 (global) and eq. 11 (local)
+ *   oracle_step          Alg. 1, FormalTraining, one pass of the while loop
+ *
+ * Every function here is pinned by tests/test_oracle_pins.py (hand-unrolled
+ * recurrence, closed forms, invariants, brute force on tiny inputs).  The four
+ * points that are readings of a silent paper (boundary case |a| == t, the code
+ * values and word layout, the initial counter value, the residual on correction
+ * iterations) are pinned only to this build's stated reading.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+
+/* 2-bit code values (this build's convention; 3 is never produced). */
+#define ORACLE_CODE_ZERO 0u
+#define ORACLE_CODE_POS 1u
+#define ORACLE_CODE_NEG 2u
+
+/* Value a 2-bit code stands for (Sec. 3.4.1: the sent value equals the
+ * threshold in magnitude).  The unused code 3 decodes to zero. */
+float oracle_dequant(uint8_t code, float t)
+{
+    if (code == ORACLE_CODE_POS) return t;
+    if (code == ORACLE_CODE_NEG) return -t;
+    return 0.0f;
+}
+
+/* Error-feedback threshold quantiser for one worker (Sec. 2.3, Sec. 3.4.1).
+ * a = r + g is what is offered; if it has reached the threshold the threshold
+ * is sent and the rest stays in the residual, otherwise nothing is sent and
+ * everything stays.  residual is updated in place, code[e] receives 0/1/2. */
+void oracle_quantize(const float *grad, float *residual, uint8_t *code, size_t n, float t)
+{
+    for (size_t e = 0; e < n; ++e) {
+        float a = residual[e] + grad[e];
+        if (a >= t) {
+            code[e] = ORACLE_CODE_POS;
+            residual[e] = a - t;
+        } else if (a <= -t) {
+            code[e] = ORACLE_CODE_NEG;
+            residual[e] = a + t;
+        } else {
+            code[e] = ORACLE_CODE_ZERO;
+            residual[e] = a;
+        }
+    }
+}
+
+/* 16 codes per 32-bit word, element e in bits [2(e%16)+1 : 2(e%16)] of word
+ * e/16; unused high bits of the last word are zero (Sec. 3.2.2, sml_buf). */
+void oracle_pack(const uint8_t *code, size_t n, uint32_t *word)
+{
+    size_t nw = (n + 15) / 16;
+    for (size_t w = 0; w < nw; ++w) word[w] = 0u;
+    for (size_t e = 0; e < n; ++e)
+        word[e / 16] |= ((uint32_t)(code[e] & 3u)) << (2 * (e % 16));
+}
+
+void oracle_unpack(const uint32_t *word, size_t n, uint8_t *code)
+{
+    for (size_t e = 0; e < n; ++e)
+        code[e] = (uint8_t)((word[e / 16] >> (2 * (e % 16))) & 3u);
+}
+
+/* Server side of a compressed iteration: decode every worker's codes back to
+ * 32 bits and add them up, workers in index order, starting from +0
+ * (Sec. 3.2.1; the sum of eq. 10). */
+void oracle_decode_sum(const uint32_t *const *word, int num_workers, float *agg, size_t n, float t)
+{
+    for (size_t e = 0; e < n; ++e) {
+        float s = 0.0f;
+        for (int j = 0; j < num_workers; ++j) {
+            uint8_t c = (uint8_t)((word[j][e / 16] >> (2 * (e % 16))) & 3u);
+            s = s + oracle_dequant(c, t);
+        }
+        agg[e] = s;
+    }
+}
+
+/* Server side of a correction iteration: the sum of the workers' 32-bit
+ * gradients, same order (eq. 1; Alg. 1, else-branch). */
+void oracle_full_sum(const float *const *grad, int num_workers, float *agg, size_t n)
+{
+    for (size_t e = 0; e < n; ++e) {
+        float s = 0.0f;
+        for (int j = 0; j < num_workers; ++j) s = s + grad[j][e];
+        agg[e] = s;
+    }
+}
+
+/* eq. 11 then eq. 10, both starting from the same global weight W_k:
+ *   Wloc = W - lr_local * g_local          (immediate, 32-bit local gradient)
+ *   W    = W - (lr_global / N) * agg       (delayed, aggregated gradient)
+ * Each is one fused multiply-add; the scale is rounded to fp32 once.
+ * w_local/grad_local may both be NULL (global rule only); agg may be NULL
+ * (local rule only). */
+void oracle_update(float *w_global, float *w_local, const float *grad_local, const float *agg,
+                   size_t n, float lr_local, float lr_global, int num_workers)
+{
+    float scale = lr_global / (float)num_workers;
+    for (size_t e = 0; e < n; ++e) {
+        float w = w_global[e];
+        if (w_local && grad_local) w_local[e] = fmaf(-lr_local, grad_local[e], w);
+        if (agg) w_global[e] = fmaf(-scale, agg[e], w);
+    }
+}
+
+/* One pass of Alg. 1's FormalTraining loop with FP/BP replaced by given
+ * gradients.  count is the loop's counter before the pass.
+ *   count % k != 0 : every worker quantises (own residual) and packs; the
+ *                    aggregate is the decoded sum.
+ *   count % k == 0 : correction iteration, no quantisation, residuals and
+ *                    packed buffers are left alone; the aggregate is the sum of
+ *                    the 32-bit gradients.
+ * The observed worker `self` updates its local weights from the pre-step global
+ * weights with its own 32-bit gradient in both cases.
+ * residual[j], grad[j], word[j] are per-worker arrays; code_scratch has n bytes.
+ * Returns 1 for a compressed iteration, 0 for a correction iteration. */
+int oracle_step(float *w_global, float *w_local, float *const *residual, const float *const *grad,
+                uint32_t *const *word, float *agg, uint8_t *code_scratch, size_t n, int num_workers,
+                int self, long count, int k, float t, float lr_local, float lr_global)
+{
+    int compressed = (count % k) != 0;
+    if (compressed) {
+        for (int j = 0; j < num_workers; ++j) {
+            oracle_quantize(grad[j], residual[j], code_scratch, n, t);
+            oracle_pack(code_scratch, n, word[j]);
+        }
+        oracle_decode_sum((const uint32_t *const *)word, num_workers, agg, n, t);
+    } else {
+        oracle_full_sum(grad, num_workers, agg, n);
+    }
+    oracle_update(w_global, w_local, grad[self], agg, n, lr_local, lr_global, num_workers);
+    return compressed;
+}

@@ -1,0 +1,68 @@
+"""The pins must be able to fail: plant one plausible mistake at a time in a
+copy of the oracle's C source (CPU only), rebuild it, and require that the pin
+suite rejects it."""
+import os
+import subprocess
+import sys
+
+import pytest
+
+from oracle import build as obuild
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+# (name, text in oracle/cdsgd_oracle.c, replacement)
+MUTANTS = [
+    ("strict_threshold", "if (a >= t) {", "if (a > t) {"),
+    ("strict_negative", "} else if (a <= -t) {", "} else if (a < -t) {"),
+    ("residual_wrong_sign", "residual[e] = a + t;", "residual[e] = a - t;"),
+    ("residual_dropped_on_send", "residual[e] = a - t;", "residual[e] = 0.0f;"),
+    ("compare_gradient_not_sum", "float a = residual[e] + grad[e];\n        if (a >= t) {",
+     "float a = residual[e] + grad[e];\n        if (grad[e] >= t) {"),
+    ("codes_swapped", "if (code == ORACLE_CODE_POS) return t;", "if (code == ORACLE_CODE_POS) return -t;"),
+    ("code3_decodes_nonzero", "if (code == ORACLE_CODE_NEG) return -t;", "if (code >= ORACLE_CODE_NEG) return -t;"),
+    ("big_endian_fields", "<< (2 * (e % 16));", "<< (2 * (15 - e % 16));"),
+    ("unpack_wrong_shift", "(word[e / 16] >> (2 * (e % 16))) & 3u);\n}", "(word[e / 16] >> (e % 16)) & 3u);\n}"),
+    ("stale_pad_bits", "for (size_t w = 0; w < nw; ++w) word[w] = 0u;", "(void)nw;"),
+    ("sum_reverse_order", "for (int j = 0; j < num_workers; ++j) {\n            uint8_t c",
+     "for (int j = num_workers - 1; j >= 0; --j) {\n            uint8_t c"),
+    ("sum_skips_a_worker", "for (int j = 0; j < num_workers; ++j) s = s + grad[j][e];",
+     "for (int j = 1; j < num_workers; ++j) s = s + grad[j][e];"),
+    ("no_average", "float scale = lr_global / (float)num_workers;", "float scale = lr_global;"),
+    ("update_sign", "fmaf(-scale, agg[e], w)", "fmaf(scale, agg[e], w)"),
+    ("local_two_roundings", "fmaf(-lr_local, grad_local[e], w)", "(w - lr_local * grad_local[e])"),
+    ("local_sees_new_global", "float w = w_global[e];\n        if (w_local && grad_local) w_local[e] = fmaf(-lr_local, grad_local[e], w);\n        if (agg) w_global[e] = fmaf(-scale, agg[e], w);",
+     "float w = w_global[e];\n        if (agg) { w = fmaf(-scale, agg[e], w); w_global[e] = w; }\n        if (w_local && grad_local) w_local[e] = fmaf(-lr_local, grad_local[e], w);"),
+    ("local_uses_aggregate_rate", "fmaf(-lr_local, grad_local[e], w)", "fmaf(-scale, grad_local[e], w)"),
+    ("mode_inverted", "int compressed = (count % k) != 0;", "int compressed = (count % k) == 0;"),
+    ("count_starts_at_one", "int compressed = (count % k) != 0;", "int compressed = ((count + 1) % k) != 0;"),
+    ("residual_flushed_on_correction", "oracle_full_sum(grad, num_workers, agg, n);",
+     "oracle_full_sum(grad, num_workers, agg, n); for (int j = 0; j < num_workers; ++j) memset(residual[j], 0, n * sizeof(float));"),
+    ("shared_residual", "oracle_quantize(grad[j], residual[j], code_scratch, n, t);",
+     "oracle_quantize(grad[j], residual[0], code_scratch, n, t);"),
+    ("local_uses_wrong_worker", "oracle_update(w_global, w_local, grad[self],", "oracle_update(w_global, w_local, grad[num_workers - 1 - self],"),
+]
+
+
+def test_mutant_list_matches_source():
+    src = open(obuild.SRC).read()
+    for name, old, _ in MUTANTS:
+        assert src.count(old) == 1, "mutant %s: anchor text not found exactly once" % name
+
+
+@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_pins_reject_mutant(tmp_path, name, old, new):
+    src = open(obuild.SRC).read()
+    assert src.count(old) == 1
+    csrc = tmp_path / "mutant.c"
+    csrc.write_text(src.replace(old, new))
+    lib = tmp_path / "libmutant.so"
+    subprocess.run(["gcc", *[f for f in obuild.CFLAGS if not f.startswith("-W")], str(csrc), "-o", str(lib), "-lm"],
+                   check=True)
+    env = dict(os.environ, CDSGD_ORACLE_LIB=str(lib))
+    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
+                        os.path.join(ROOT, "tests", "test_oracle_pins.py"),
+                        "-k", "not bruteforce or 0.125"],
+                       cwd=ROOT, env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert r.returncode == 1, "pins did not catch mutant %s:\n%s" % (name, r.stdout[-1500:])
+    assert "failed" in r.stdout
