@@ -1,0 +1,157 @@
+/*
+ * cdsgd.h -- C ABI of the CD-SGD per-step data-parallel hot path on one GPU.
+ *
+ * What is computed (arxiv 2106.10796): in every iteration of the formal
+ * training phase (Alg. 1) a worker
+ *   - updates its local weights at once with its own 32-bit gradient (eq. 11),
+ *   - on compressed iterations (count % k != 0) quantises residual + gradient
+ *     against a threshold into 2-bit codes, keeping the error in the residual
+ *     buffer (Sec. 2.3, Sec. 3.4.1), and writes the codes 16 to a 32-bit word
+ *     (Sec. 3.2.2, sml_buf),
+ *   - and the global weights are updated with the sum over all N workers of the
+ *     decoded codes (Sec. 3.2.1; eq. 10), or, on correction iterations
+ *     (count % k == 0), with the sum of the 32-bit gradients (Sec. 3.1).
+ *
+ * Conventions common to every call
+ *   memory     All data pointers are DEVICE pointers owned by the caller unless
+ *              a parameter says "host".  The library never frees or keeps them,
+ *              except that a plan keeps (borrows) the pointers it was built from.
+ *   alignment  fp32 buffers must be 16-byte aligned, packed buffers 4-byte
+ *              aligned (CDSGD_ERR_ALIGN otherwise).
+ *   stream     hip_stream is a hipStream_t passed as void* (NULL = the null
+ *              stream).  Work is enqueued and the call returns; nothing
+ *              synchronises.
+ *   errors     The return value is a cdsgd_status.  Arguments are checked on the
+ *              host before any HIP call; on an error nothing has been enqueued.
+ *   layout     A packed stream of n elements has cdsgd_packed_words(n) words.
+ *              Element e is the 2-bit field at bits [2(e%16)+1 : 2(e%16)] of
+ *              word e/16: 00 nothing sent, 01 +threshold, 10 -threshold; 11 is
+ *              never written and reads as nothing sent.  Unused bits of the last
+ *              word are written as 0.
+ *   numbers    fp32, round to nearest even, denormals kept.  Sums over workers
+ *              run in worker order 0..N-1 starting from +0.  Each weight update
+ *              is one fused multiply-add; lr_global / num_workers is rounded to
+ *              fp32 once.  Results do not depend on the launch shape.
+ */
+#ifndef CDSGD_H
+#define CDSGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CDSGD_OK = 0,
+    CDSGD_ERR_NULL = 1,    /* a required pointer is NULL */
+    CDSGD_ERR_SIZE = 2,    /* n == 0, num_tensors < 1, or a size too large for the launch */
+    CDSGD_ERR_PARAM = 3,   /* threshold not finite or <= 0, k < 1, step < 0, rate not finite */
+    CDSGD_ERR_ALIGN = 4,   /* pointer alignment (see above) */
+    CDSGD_ERR_WORKERS = 5, /* num_workers < 1 or > CDSGD_MAX_WORKERS, self out of range */
+    CDSGD_ERR_DEVICE = 6   /* a HIP call failed (allocation, copy, launch) */
+} cdsgd_status;
+
+#define CDSGD_MAX_WORKERS 64
+
+/* Number of 32-bit words of a packed stream of n elements: ceil(n / 16). */
+size_t cdsgd_packed_words(size_t n);
+
+/* Static, NUL-terminated description of a status code. */
+const char *cdsgd_status_string(int status);
+
+/*
+ * Quantise and pack one worker's gradient (Sec. 2.3, Sec. 3.4.1, Sec. 3.2.2).
+ * Per element: a = residual + grad; a >= t sends +t and keeps a - t; a <= -t
+ * sends -t and keeps a + t; otherwise nothing is sent and a is kept.
+ *   grad      in   fp32[n]
+ *   residual  i/o  fp32[n], updated in place; must not alias grad
+ *   packed    out  uint32[cdsgd_packed_words(n)], fully overwritten
+ */
+int cdsgd_quantize_pack(const float *grad, float *residual, uint32_t *packed, size_t n,
+                        float threshold, void *hip_stream);
+
+/*
+ * Decode N workers' packed streams to 32 bits and add them up in worker order
+ * (Sec. 3.2.1; the sum of eq. 10).
+ *   packed  in   HOST array of num_workers DEVICE pointers, each to
+ *                uint32[cdsgd_packed_words(n)]; read during the call only
+ *   agg     out  fp32[n]
+ */
+int cdsgd_decode_sum(const uint32_t *const *packed, int num_workers, float *agg, size_t n,
+                     float threshold, void *hip_stream);
+
+/*
+ * The two update rules, both from the same pre-call global weight (eq. 10, 11):
+ *   w_local[e]  = fma(-lr_local, grad_local[e], w_global[e])
+ *   w_global[e] = fma(-(lr_global / num_workers), agg[e], w_global[e])
+ *   w_global    i/o  fp32[n]
+ *   w_local     out  fp32[n]; must not alias w_global
+ *   grad_local  in   fp32[n]; w_local and grad_local may both be NULL: global rule only
+ *   agg         in   fp32[n]; may be NULL: local rule only, w_global is left alone
+ */
+int cdsgd_update(float *w_global, float *w_local, const float *grad_local, const float *agg,
+                 size_t n, float lr_local, float lr_global, int num_workers, void *hip_stream);
+
+/*
+ * Fused step over a layer list (Alg. 1, FormalTraining, one pass): one kernel
+ * launch covers every tensor, and each gradient, residual and weight element
+ * crosses HBM once.
+ *
+ * One entry per tensor.  packed_self receives this worker's codes on compressed
+ * steps (what would be pushed).  agg_full is the fp32 sum over all N workers of
+ * this tensor's 32-bit gradients, read on correction steps only; it may be NULL
+ * if the plan is never used for a correction step.
+ */
+typedef struct {
+    float *w_global;        /* i/o fp32[n] */
+    float *w_local;         /* out fp32[n] */
+    float *residual;        /* i/o fp32[n] (compressed steps) */
+    const float *grad;      /* in  fp32[n] this worker's gradient */
+    uint32_t *packed_self;  /* out uint32[cdsgd_packed_words(n)] (compressed steps) */
+    const float *agg_full;  /* in  fp32[n] (correction steps) or NULL */
+    size_t n;
+} cdsgd_tensor;
+
+typedef struct cdsgd_plan cdsgd_plan;
+
+/*
+ * Build a plan: copies the layer list, the peers' pointers and a chunk table to
+ * the device (one small allocation, one synchronous copy; the only call that
+ * allocates).  The plan borrows every data pointer: the buffers must stay alive
+ * and in place while the plan is used.
+ *   tensors      host array [num_tensors]
+ *   peers        host array [num_workers] of host arrays [num_tensors] of device
+ *                pointers: peers[j][i] is worker j's packed stream for tensor i
+ *                (what would be pulled from the server side).  Row `self` is
+ *                ignored and may be NULL: this worker's codes never leave
+ *                registers before they are summed.  peers may be NULL when
+ *                num_workers == 1.
+ *   self         this worker's position in the sum order, 0 <= self < num_workers
+ *   out          receives the plan
+ */
+int cdsgd_plan_create(const cdsgd_tensor *tensors, int num_tensors,
+                      const uint32_t *const *const *peers, int num_workers, int self,
+                      cdsgd_plan **out);
+
+/* Frees the plan's device table.  NULL is accepted. */
+int cdsgd_plan_destroy(cdsgd_plan *plan);
+
+/*
+ * One pass of Alg. 1's loop for every tensor of the plan, `step` being the
+ * loop's counter before the pass (it starts at 0).
+ *   step % k != 0  compressed: quantise + pack own gradient (residual and
+ *                  packed_self written), decode and sum the N streams with the
+ *                  own codes at position `self`, then both update rules.
+ *   step % k == 0  correction: no quantisation, residual and packed_self are not
+ *                  touched; both update rules with agg_full as the aggregate
+ *                  (CDSGD_ERR_NULL if a tensor has none).
+ */
+int cdsgd_step_fused(cdsgd_plan *plan, long step, int k, float threshold, float lr_local,
+                     float lr_global, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CDSGD_H */

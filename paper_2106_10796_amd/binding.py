@@ -1,0 +1,184 @@
+"""ctypes binding of libcdsgd.so: argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI (include/cdsgd.h).
+PyTorch is used for device memory and the current stream, nothing else.  There
+is no fallback: a missing library is an error.
+"""
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libcdsgd.so")
+
+MAX_WORKERS = 64
+OK, ERR_NULL, ERR_SIZE, ERR_PARAM, ERR_ALIGN, ERR_WORKERS, ERR_DEVICE = range(7)
+
+
+class CdsgdError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        msg = lib().cdsgd_status_string(int(status)).decode()
+        super().__init__("%s: status %d (%s)" % (where, self.status, msg))
+
+
+class cdsgd_tensor(ctypes.Structure):
+    _fields_ = [("w_global", ctypes.c_void_p), ("w_local", ctypes.c_void_p),
+                ("residual", ctypes.c_void_p), ("grad", ctypes.c_void_p),
+                ("packed_self", ctypes.c_void_p), ("agg_full", ctypes.c_void_p),
+                ("n", ctypes.c_size_t)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C-ABI library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libcdsgd.so is not built (run: python -m paper_2106_10796_amd.build); "
+                               "there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, f, i = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float, ctypes.c_int
+        L.cdsgd_packed_words.restype = sz
+        L.cdsgd_packed_words.argtypes = [sz]
+        L.cdsgd_status_string.restype = ctypes.c_char_p
+        L.cdsgd_status_string.argtypes = [i]
+        L.cdsgd_quantize_pack.restype = i
+        L.cdsgd_quantize_pack.argtypes = [vp, vp, vp, sz, f, vp]
+        L.cdsgd_decode_sum.restype = i
+        L.cdsgd_decode_sum.argtypes = [ctypes.POINTER(vp), i, vp, sz, f, vp]
+        L.cdsgd_update.restype = i
+        L.cdsgd_update.argtypes = [vp, vp, vp, vp, sz, f, f, i, vp]
+        L.cdsgd_plan_create.restype = i
+        L.cdsgd_plan_create.argtypes = [ctypes.POINTER(cdsgd_tensor), i, ctypes.POINTER(ctypes.POINTER(vp)),
+                                        i, i, ctypes.POINTER(vp)]
+        L.cdsgd_plan_destroy.restype = i
+        L.cdsgd_plan_destroy.argtypes = [vp]
+        L.cdsgd_step_fused.restype = i
+        L.cdsgd_step_fused.argtypes = [vp, ctypes.c_long, i, f, f, f, vp]
+        _lib = L
+    return _lib
+
+
+def packed_words(n: int) -> int:
+    return int(lib().cdsgd_packed_words(int(n)))
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype, n=None, name="tensor"):
+    if t is None:
+        return None
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous CUDA tensor of %s" % (name, dtype))
+    if n is not None and t.numel() != n:
+        raise ValueError("%s has %d elements, expected %d" % (name, t.numel(), n))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+# packed streams are stored in int32 tensors (torch has no full uint32 support); the bits are what matter
+PACKED_DTYPE = torch.int32
+
+
+def new_packed(n: int, device="cuda") -> torch.Tensor:
+    return torch.empty(packed_words(n), dtype=PACKED_DTYPE, device=device)
+
+
+def _check(status, where):
+    if status != OK:
+        raise CdsgdError(status, where)
+
+
+def cdsgd_quantize_pack(grad, residual, packed, threshold):
+    n = grad.numel()
+    st = lib().cdsgd_quantize_pack(_dev(grad, torch.float32, None, "grad"),
+                                   _dev(residual, torch.float32, n, "residual"),
+                                   _dev(packed, PACKED_DTYPE, packed_words(n), "packed"),
+                                   n, float(threshold), _stream())
+    _check(st, "cdsgd_quantize_pack")
+
+
+def cdsgd_decode_sum(packed_list, agg, threshold):
+    n = agg.numel()
+    N = len(packed_list)
+    arr = (ctypes.c_void_p * max(N, 1))()
+    for j, p in enumerate(packed_list):
+        arr[j] = _dev(p, PACKED_DTYPE, packed_words(n), "packed[%d]" % j)
+    st = lib().cdsgd_decode_sum(arr, N, _dev(agg, torch.float32, None, "agg"), n, float(threshold), _stream())
+    _check(st, "cdsgd_decode_sum")
+
+
+def cdsgd_update(w_global, w_local, grad_local, agg, lr_local, lr_global, num_workers):
+    n = w_global.numel()
+    st = lib().cdsgd_update(_dev(w_global, torch.float32, None, "w_global"),
+                            _dev(w_local, torch.float32, n, "w_local"),
+                            _dev(grad_local, torch.float32, n, "grad_local"),
+                            _dev(agg, torch.float32, n, "agg"),
+                            n, float(lr_local), float(lr_global), int(num_workers), _stream())
+    _check(st, "cdsgd_update")
+
+
+class Plan:
+    """A fused-step plan over a layer list (cdsgd_plan_create / cdsgd_step_fused / cdsgd_plan_destroy).
+
+    tensors: list of dicts with keys w_global, w_local, residual, grad, packed_self and
+    optionally agg_full (torch CUDA tensors).  peers: list over workers of lists over
+    tensors of packed tensors; the entry for `self_rank` may be None.  The plan keeps
+    references to every tensor so that the borrowed pointers stay valid.
+    """
+
+    def __init__(self, tensors, peers, num_workers, self_rank):
+        T = len(tensors)
+        self._keep = (tensors, peers)
+        arr = (cdsgd_tensor * max(T, 1))()
+        for i, t in enumerate(tensors):
+            n = t["w_global"].numel()
+            arr[i].w_global = _dev(t["w_global"], torch.float32, None, "w_global").value
+            arr[i].w_local = _dev(t["w_local"], torch.float32, n, "w_local").value
+            arr[i].residual = _dev(t["residual"], torch.float32, n, "residual").value
+            arr[i].grad = _dev(t["grad"], torch.float32, n, "grad").value
+            arr[i].packed_self = _dev(t["packed_self"], PACKED_DTYPE, packed_words(n), "packed_self").value
+            af = t.get("agg_full")
+            arr[i].agg_full = _dev(af, torch.float32, n, "agg_full").value if af is not None else None
+            arr[i].n = n
+        rows = (ctypes.POINTER(ctypes.c_void_p) * max(num_workers, 1))()
+        self._rows = []
+        if peers is not None:
+            for j in range(num_workers):
+                if peers[j] is None:
+                    rows[j] = ctypes.POINTER(ctypes.c_void_p)()
+                    continue
+                row = (ctypes.c_void_p * max(T, 1))()
+                for i in range(T):
+                    n = tensors[i]["w_global"].numel()
+                    row[i] = _dev(peers[j][i], PACKED_DTYPE, packed_words(n), "peers[%d][%d]" % (j, i)).value
+                self._rows.append(row)
+                rows[j] = ctypes.cast(row, ctypes.POINTER(ctypes.c_void_p))
+        handle = ctypes.c_void_p()
+        st = lib().cdsgd_plan_create(arr, T, rows if peers is not None else None, int(num_workers),
+                                     int(self_rank), ctypes.byref(handle))
+        _check(st, "cdsgd_plan_create")
+        self._handle = handle
+        self.num_workers = int(num_workers)
+
+    def step(self, step, k, threshold, lr_local, lr_global):
+        st = lib().cdsgd_step_fused(self._handle, int(step), int(k), float(threshold), float(lr_local),
+                                    float(lr_global), _stream())
+        _check(st, "cdsgd_step_fused")
+
+    def destroy(self):
+        if self._handle is not None and self._handle.value:
+            lib().cdsgd_plan_destroy(self._handle)
+        self._handle = None
+        self._keep = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

@@ -1,0 +1,785 @@
+// CD-SGD per-step data-parallel hot path for gfx950 (MI355X): kernels and C ABI.
+//
+// Work decomposition.  The unit of work of one lane is a "quad": four
+// consecutive fp32 elements = one 128-bit load/store per buffer = one byte of
+// the packed stream (four 2-bit codes; element e of a tensor is bits
+// [2(e%4)+1 : 2(e%4)] of packed byte e/4, which is the little-endian view of
+// the 32-bit-word layout in cdsgd.h).  A workgroup of kBlock lanes owns a
+// "chunk" of kQpl * kBlock consecutive quads; lane `tid` takes quads
+// j*kBlock + tid, so every wave instruction touches one contiguous 1 KiB
+// (fp32 buffers) or 64 B (packed streams) span: all traffic is fully
+// coalesced and no cross-lane exchange is needed to build or to read the
+// packed words.
+//
+// The path is elementwise and HBM-bound: no LDS tiles, no MFMA.  Each of
+// grad / residual / w_global is read once and each of residual / w_global /
+// w_local is written once per step.
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "cdsgd.h"
+
+#ifndef CDSGD_BLOCK
+#define CDSGD_BLOCK 256
+#endif
+#ifndef CDSGD_QPL
+#define CDSGD_QPL 4
+#endif
+#ifndef CDSGD_NT
+#define CDSGD_NT 0
+#endif
+#ifndef CDSGD_PEER_BATCH
+#define CDSGD_PEER_BATCH 8
+#endif
+
+namespace {
+
+constexpr unsigned kBlock = CDSGD_BLOCK;          // lanes per workgroup
+constexpr unsigned kQpl = CDSGD_QPL;              // quads per lane
+constexpr unsigned kChunkQuads = kBlock * kQpl;   // quads (= packed bytes) per chunk
+constexpr unsigned kChunkElems = kChunkQuads * 4; // elements per chunk
+constexpr int kPeerBatch = CDSGD_PEER_BATCH;      // peers whose bytes are in flight together
+static_assert(kQpl == 1 || kQpl == 2 || kQpl == 4, "a lane's packed bytes must fit one register");
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------
+// 128-bit loads / stores, with the ragged end of a tensor handled per element
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ f4 ld4(const float *base, unsigned qi)
+{
+    const f4 *p = reinterpret_cast<const f4 *>(base) + qi;
+#if CDSGD_NT
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
+
+__device__ __forceinline__ void st4(float *base, unsigned qi, f4 v)
+{
+    f4 *p = reinterpret_cast<f4 *>(base) + qi;
+#if CDSGD_NT
+    __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
+}
+
+// cnt = number of elements of this quad that exist (4 in the interior).
+template <bool G>
+__device__ __forceinline__ f4 ld4g(const float *base, unsigned qi, int cnt)
+{
+    if (!G || cnt == 4) return ld4(base, qi);
+    f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+    const float *p = base + 4u * qi;
+    if (cnt > 0) v.x = p[0];
+    if (cnt > 1) v.y = p[1];
+    if (cnt > 2) v.z = p[2];
+    return v;
+}
+
+template <bool G>
+__device__ __forceinline__ void st4g(float *base, unsigned qi, int cnt, f4 v)
+{
+    if (!G || cnt == 4) {
+        st4(base, qi, v);
+        return;
+    }
+    float *p = base + 4u * qi;
+    if (cnt > 0) p[0] = v.x;
+    if (cnt > 1) p[1] = v.y;
+    if (cnt > 2) p[2] = v.z;
+}
+
+template <bool G>
+__device__ __forceinline__ int quad_count(unsigned rem_elems, unsigned qi)
+{
+    if (!G) return 4;
+    int c = (int)rem_elems - (int)(4u * qi);
+    return c < 0 ? 0 : (c > 4 ? 4 : c);
+}
+
+// ---------------------------------------------------------------------------
+// a1 + a2: error-feedback threshold quantiser (Sec. 2.3, Sec. 3.4.1)
+// ---------------------------------------------------------------------------
+// a = r + g; |a| >= t sends sign(a)*t and keeps the rest.  `sent` is what the
+// code stands for (+t, -t or +0); a - sent is bit-identical to a - t, a + t and
+// a in the three cases.  Returns the 2-bit code (1 = +t, 2 = -t).
+__device__ __forceinline__ unsigned quantize1(float g, float &r, float t, float &sent)
+{
+    const float a = r + g;
+    const bool pos = a >= t;
+    const bool neg = a <= -t;
+    sent = pos ? t : (neg ? -t : 0.0f);
+    r = a - sent;
+    return pos ? 1u : (neg ? 2u : 0u);
+}
+
+// One quad: residual updated in place, returns the packed byte.
+__device__ __forceinline__ unsigned quantize_quad(const f4 g, f4 &r, float t, f4 &sent)
+{
+    float s0, s1, s2, s3, r0 = r.x, r1 = r.y, r2 = r.z, r3 = r.w;
+    const unsigned c0 = quantize1(g.x, r0, t, s0);
+    const unsigned c1 = quantize1(g.y, r1, t, s1);
+    const unsigned c2 = quantize1(g.z, r2, t, s2);
+    const unsigned c3 = quantize1(g.w, r3, t, s3);
+    r = f4{r0, r1, r2, r3};
+    sent = f4{s0, s1, s2, s3};
+    return c0 | (c1 << 2) | (c2 << 4) | (c3 << 6);
+}
+
+// ---------------------------------------------------------------------------
+// a4: decode-and-sum (Sec. 3.2.1; sum of eq. 10)
+// ---------------------------------------------------------------------------
+// A lane keeps the packed bytes of its kQpl quads of one worker in one
+// register: byte j = quad j.
+
+// Bytes of one worker for this lane's quads.
+template <bool G>
+__device__ __forceinline__ unsigned load_codes(const uint8_t *stream, unsigned tid, unsigned rem_bytes)
+{
+    unsigned w = 0;
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) {
+        const unsigned qi = j * kBlock + tid;
+        unsigned b = 0;
+        if (!G || qi < rem_bytes) b = stream[qi];
+        w |= b << (8 * j);
+    }
+    return w;
+}
+
+// Literal fp32 chain: agg += value(code) for the 4*kQpl elements of this lane,
+// one rounded add per element.  The codes are first rewritten, 16 at a time,
+// as 2-bit two's-complement counts (01 -> +1, 10 -> -1, 00 and 11 -> 0) so
+// that one signed bit-field extract yields the multiplier.
+__device__ __forceinline__ void chain_codes(f4 (&agg)[kQpl], unsigned w, float t)
+{
+    const unsigned x = w & 0x55555555u;
+    const unsigned y = (w >> 1) & 0x55555555u;
+    const unsigned lo = x ^ y;
+    const unsigned hi = y & ~x;
+    const unsigned s = lo | (hi << 1);
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) {
+#pragma unroll
+        for (unsigned c = 0; c < 4; ++c) {
+            const int m = ((int)(s << (30u - (8u * j + 2u * c)))) >> 30;
+            agg[j][c] = __builtin_fmaf((float)m, t, agg[j][c]);
+        }
+    }
+}
+
+// Count form for thresholds that are powers of two (every partial sum of the
+// chain is then exact, so sum == count * t bit for bit).  Per worker the 16
+// codes become biased counts (2 + value) in 2-bit fields without borrows, and
+// are added into four registers of byte-wide fields: acc[c] byte j belongs to
+// element c of quad j.
+__device__ __forceinline__ void count_codes(unsigned (&acc)[4], unsigned w)
+{
+    const unsigned z = ((w & 0x55555555u) | 0xAAAAAAAAu) - ((w >> 1) & 0x55555555u);
+    acc[0] += z & 0x03030303u;
+    acc[1] += (z >> 2) & 0x03030303u;
+    acc[2] += (z >> 4) & 0x03030303u;
+    acc[3] += (z >> 6) & 0x03030303u;
+}
+
+// acc holds 2*num_summed + sum of values; bias_t = -(2*num_summed)*t.
+__device__ __forceinline__ void counts_to_sum(f4 (&agg)[kQpl], const unsigned (&acc)[4], float t,
+                                              float bias_t)
+{
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) {
+#pragma unroll
+        for (unsigned c = 0; c < 4; ++c) {
+            const float cnt = (float)((acc[c] >> (8u * j)) & 0xFFu);
+            agg[j][c] = __builtin_fmaf(cnt, t, bias_t);
+        }
+    }
+}
+
+// Sum workers [p_begin, p_end) of a pointer table into agg (chain) or acc (count),
+// kPeerBatch streams in flight at a time.
+template <bool G, bool POW2>
+__device__ __forceinline__ void sum_streams(f4 (&agg)[kQpl], unsigned (&acc)[4],
+                                            const uint8_t *const *__restrict__ tab, int p_begin,
+                                            int p_end, size_t quad0, unsigned tid,
+                                            unsigned rem_bytes, float t)
+{
+    int p = p_begin;
+    for (; p + kPeerBatch <= p_end; p += kPeerBatch) {
+        unsigned w[kPeerBatch];
+#pragma unroll
+        for (int i = 0; i < kPeerBatch; ++i) w[i] = load_codes<G>(tab[p + i] + quad0, tid, rem_bytes);
+#pragma unroll
+        for (int i = 0; i < kPeerBatch; ++i) {
+            if (POW2) count_codes(acc, w[i]);
+            else chain_codes(agg, w[i], t);
+        }
+    }
+    if (kPeerBatch > 4 && p + 4 <= p_end) {
+        unsigned w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = load_codes<G>(tab[p + i] + quad0, tid, rem_bytes);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (POW2) count_codes(acc, w[i]);
+            else chain_codes(agg, w[i], t);
+        }
+        p += 4;
+    }
+    for (; p < p_end; ++p) {
+        const unsigned w = load_codes<G>(tab[p] + quad0, tid, rem_bytes);
+        if (POW2) count_codes(acc, w);
+        else chain_codes(agg, w, t);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// device-side tables of a plan
+// ---------------------------------------------------------------------------
+// How a tensor of n elements splits into chunks: `full_chunks` chunks hold
+// kChunkElems elements each; if anything is left, one more chunk holds the
+// ragged end: tail_elems elements (< kChunkElems) and tail_bytes bytes of the
+// packed stream (the bytes of the last word past the last element included).
+// Everything is 32-bit and uniform, so the interior/tail decision is a scalar
+// compare on the chunk number.
+struct Extent {
+    unsigned full_chunks;
+    unsigned tail_elems;
+    unsigned tail_bytes;
+    unsigned pad_;
+};
+
+struct TensorDesc {
+    float *w_global;
+    float *w_local;
+    float *residual;
+    const float *grad;
+    uint8_t *packed_self;
+    const float *agg_full;
+    Extent ext;
+};
+
+struct ChunkRef {
+    unsigned tensor;  // index into the TensorDesc table
+    unsigned chunk;   // chunk number inside that tensor
+};
+
+// ---------------------------------------------------------------------------
+// kernels
+// ---------------------------------------------------------------------------
+
+// a1-a3 for one tensor.
+template <bool G>
+__device__ __forceinline__ void quantize_pack_chunk(const float *__restrict__ grad,
+                                                    float *__restrict__ resid,
+                                                    uint8_t *__restrict__ packed, unsigned rem_elems,
+                                                    unsigned rem_bytes, float t)
+{
+    const unsigned tid = threadIdx.x;
+    f4 g[kQpl], r[kQpl];
+    int cnt[kQpl];
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) {
+        const unsigned qi = j * kBlock + tid;
+        cnt[j] = quad_count<G>(rem_elems, qi);
+        g[j] = ld4g<G>(grad, qi, cnt[j]);
+        r[j] = ld4g<G>(resid, qi, cnt[j]);
+    }
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) {
+        const unsigned qi = j * kBlock + tid;
+        f4 sent;
+        const unsigned b = quantize_quad(g[j], r[j], t, sent);
+        st4g<G>(resid, qi, cnt[j], r[j]);
+        if (!G || qi < rem_bytes) packed[qi] = (uint8_t)b;
+    }
+}
+
+__global__ __launch_bounds__(CDSGD_BLOCK) void k_quantize_pack(const float *__restrict__ grad,
+                                                               float *__restrict__ resid,
+                                                               uint8_t *__restrict__ packed, Extent ext,
+                                                               float t)
+{
+    const unsigned chunk = blockIdx.x;
+    const size_t quad0 = (size_t)chunk * kChunkQuads;
+    grad += 4 * quad0;
+    resid += 4 * quad0;
+    packed += quad0;
+    if (chunk < ext.full_chunks) quantize_pack_chunk<false>(grad, resid, packed, kChunkElems, kChunkQuads, t);
+    else quantize_pack_chunk<true>(grad, resid, packed, ext.tail_elems, ext.tail_bytes, t);
+}
+
+// a4 for one tensor; the worker pointers travel in the kernel arguments.
+struct StreamTable {
+    const uint8_t *p[CDSGD_MAX_WORKERS];
+};
+
+template <bool G, bool POW2>
+__device__ __forceinline__ void decode_sum_chunk(const StreamTable &tab, int num_workers,
+                                                 float *__restrict__ agg_out, size_t quad0,
+                                                 unsigned rem_elems, unsigned rem_bytes, float t,
+                                                 float bias_t)
+{
+    const unsigned tid = threadIdx.x;
+    f4 agg[kQpl];
+    unsigned acc[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) agg[j] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+    sum_streams<G, POW2>(agg, acc, tab.p, 0, num_workers, quad0, tid, rem_bytes, t);
+    if (POW2) counts_to_sum(agg, acc, t, bias_t);
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) {
+        const unsigned qi = j * kBlock + tid;
+        st4g<G>(agg_out, qi, quad_count<G>(rem_elems, qi), agg[j]);
+    }
+}
+
+template <bool POW2>
+__global__ __launch_bounds__(CDSGD_BLOCK) void k_decode_sum(StreamTable tab, int num_workers,
+                                                            float *__restrict__ agg, Extent ext, float t,
+                                                            float bias_t)
+{
+    const unsigned chunk = blockIdx.x;
+    const size_t quad0 = (size_t)chunk * kChunkQuads;
+    agg += 4 * quad0;
+    if (chunk < ext.full_chunks)
+        decode_sum_chunk<false, POW2>(tab, num_workers, agg, quad0, kChunkElems, kChunkQuads, t, bias_t);
+    else
+        decode_sum_chunk<true, POW2>(tab, num_workers, agg, quad0, ext.tail_elems, ext.tail_bytes, t, bias_t);
+}
+
+// a5 + a6 (eq. 10, eq. 11), both from the weight that was loaded.
+template <bool G, bool LOCAL, bool GLOBAL>
+__device__ __forceinline__ void update_chunk(float *__restrict__ wg, float *__restrict__ wl,
+                                             const float *__restrict__ grad,
+                                             const float *__restrict__ agg, unsigned rem_elems,
+                                             float lr_local, float scale)
+{
+    const unsigned tid = threadIdx.x;
+    f4 w[kQpl], g[kQpl], a[kQpl];
+    int cnt[kQpl];
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) {
+        const unsigned qi = j * kBlock + tid;
+        cnt[j] = quad_count<G>(rem_elems, qi);
+        w[j] = ld4g<G>(wg, qi, cnt[j]);
+        if (LOCAL) g[j] = ld4g<G>(grad, qi, cnt[j]);
+        if (GLOBAL) a[j] = ld4g<G>(agg, qi, cnt[j]);
+    }
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) {
+        const unsigned qi = j * kBlock + tid;
+        if (LOCAL) {
+            f4 v;
+#pragma unroll
+            for (unsigned c = 0; c < 4; ++c) v[c] = __builtin_fmaf(-lr_local, g[j][c], w[j][c]);
+            st4g<G>(wl, qi, cnt[j], v);
+        }
+        if (GLOBAL) {
+            f4 v;
+#pragma unroll
+            for (unsigned c = 0; c < 4; ++c) v[c] = __builtin_fmaf(-scale, a[j][c], w[j][c]);
+            st4g<G>(wg, qi, cnt[j], v);
+        }
+    }
+}
+
+template <bool LOCAL, bool GLOBAL>
+__global__ __launch_bounds__(CDSGD_BLOCK) void k_update(float *__restrict__ wg, float *__restrict__ wl,
+                                                        const float *__restrict__ grad,
+                                                        const float *__restrict__ agg, Extent ext,
+                                                        float lr_local, float scale)
+{
+    const unsigned chunk = blockIdx.x;
+    const size_t quad0 = (size_t)chunk * kChunkQuads;
+    wg += 4 * quad0;
+    if (LOCAL) {
+        wl += 4 * quad0;
+        grad += 4 * quad0;
+    }
+    if (GLOBAL) agg += 4 * quad0;
+    if (chunk < ext.full_chunks) update_chunk<false, LOCAL, GLOBAL>(wg, wl, grad, agg, kChunkElems, lr_local, scale);
+    else update_chunk<true, LOCAL, GLOBAL>(wg, wl, grad, agg, ext.tail_elems, lr_local, scale);
+}
+
+// Fused compressed step (a1-a6) for one chunk of one tensor.
+template <bool G, bool POW2>
+__device__ __forceinline__ void fused_chunk(const TensorDesc &d, const uint8_t *const *__restrict__ peers,
+                                            int num_peers, int self, size_t quad0, unsigned rem_elems,
+                                            unsigned rem_bytes, float t, float lr_local, float scale,
+                                            float bias_t)
+{
+    const unsigned tid = threadIdx.x;
+    const float *__restrict__ grad = d.grad + 4 * quad0;
+    float *__restrict__ resid = d.residual + 4 * quad0;
+    float *__restrict__ wg = d.w_global + 4 * quad0;
+    float *__restrict__ wl = d.w_local + 4 * quad0;
+    uint8_t *__restrict__ pself = d.packed_self + quad0;
+
+    f4 g[kQpl], r[kQpl], w[kQpl], agg[kQpl], sent[kQpl];
+    int cnt[kQpl];
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) {
+        const unsigned qi = j * kBlock + tid;
+        cnt[j] = quad_count<G>(rem_elems, qi);
+        g[j] = ld4g<G>(grad, qi, cnt[j]);
+        r[j] = ld4g<G>(resid, qi, cnt[j]);
+    }
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) {
+        const unsigned qi = j * kBlock + tid;
+        w[j] = ld4g<G>(wg, qi, cnt[j]);
+        agg[j] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+    }
+
+    // own codes: quantise, keep the residual, write what would be pushed
+    unsigned own = 0;
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) {
+        const unsigned qi = j * kBlock + tid;
+        const unsigned b = quantize_quad(g[j], r[j], t, sent[j]);
+        st4g<G>(resid, qi, cnt[j], r[j]);
+        if (!G || qi < rem_bytes) pself[qi] = (uint8_t)b;
+        own |= b << (8 * j);
+    }
+
+    // aggregate: workers 0..self-1, own codes, workers self+1..N-1
+    unsigned acc[4] = {0u, 0u, 0u, 0u};
+    sum_streams<G, POW2>(agg, acc, peers, 0, self, quad0, tid, rem_bytes, t);
+    if (POW2) {
+        count_codes(acc, own);
+    } else {
+#pragma unroll
+        for (unsigned j = 0; j < kQpl; ++j) agg[j] = agg[j] + sent[j];
+    }
+    sum_streams<G, POW2>(agg, acc, peers, self, num_peers, quad0, tid, rem_bytes, t);
+    if (POW2) counts_to_sum(agg, acc, t, bias_t);
+
+    // eq. 11 and eq. 10 from the same loaded weight
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) {
+        const unsigned qi = j * kBlock + tid;
+        f4 vl, vg;
+#pragma unroll
+        for (unsigned c = 0; c < 4; ++c) {
+            vl[c] = __builtin_fmaf(-lr_local, g[j][c], w[j][c]);
+            vg[c] = __builtin_fmaf(-scale, agg[j][c], w[j][c]);
+        }
+        st4g<G>(wl, qi, cnt[j], vl);
+        st4g<G>(wg, qi, cnt[j], vg);
+    }
+}
+
+// peers: [num_tensors][num_peers] pointers, this worker's own row left out.
+template <bool POW2>
+__global__ __launch_bounds__(CDSGD_BLOCK) void k_fused_compressed(const TensorDesc *__restrict__ tensors,
+                                                                  const ChunkRef *__restrict__ chunks,
+                                                                  const uint8_t *const *__restrict__ peers,
+                                                                  int num_peers, int self, float t,
+                                                                  float lr_local, float scale, float bias_t)
+{
+    const ChunkRef cr = chunks[blockIdx.x];
+    const TensorDesc d = tensors[cr.tensor];
+    const size_t quad0 = (size_t)cr.chunk * kChunkQuads;
+    const uint8_t *const *tp = peers + (size_t)cr.tensor * (size_t)num_peers;
+    if (cr.chunk < d.ext.full_chunks)
+        fused_chunk<false, POW2>(d, tp, num_peers, self, quad0, kChunkElems, kChunkQuads, t, lr_local, scale, bias_t);
+    else
+        fused_chunk<true, POW2>(d, tp, num_peers, self, quad0, d.ext.tail_elems, d.ext.tail_bytes, t, lr_local,
+                                scale, bias_t);
+}
+
+// Correction step over the layer list: no quantisation, agg_full is the aggregate.
+__global__ __launch_bounds__(CDSGD_BLOCK) void k_fused_correction(const TensorDesc *__restrict__ tensors,
+                                                                  const ChunkRef *__restrict__ chunks,
+                                                                  float lr_local, float scale)
+{
+    const ChunkRef cr = chunks[blockIdx.x];
+    const TensorDesc d = tensors[cr.tensor];
+    const size_t quad0 = (size_t)cr.chunk * kChunkQuads;
+    float *wg = d.w_global + 4 * quad0;
+    float *wl = d.w_local + 4 * quad0;
+    const float *grad = d.grad + 4 * quad0;
+    const float *agg = d.agg_full + 4 * quad0;
+    if (cr.chunk < d.ext.full_chunks) update_chunk<false, true, true>(wg, wl, grad, agg, kChunkElems, lr_local, scale);
+    else update_chunk<true, true, true>(wg, wl, grad, agg, d.ext.tail_elems, lr_local, scale);
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+inline unsigned long long packed_bytes_of(size_t n) { return 4ull * ((n + 15) / 16); }
+
+// Chunks needed to cover a tensor's packed stream (which covers its elements):
+// n / kChunkElems full ones, plus one for the ragged end if there is one.
+inline unsigned long long chunks_of(size_t n) { return (packed_bytes_of(n) + kChunkQuads - 1) / kChunkQuads; }
+
+inline Extent extent_of(size_t n)
+{
+    Extent e;
+    const unsigned long long full = n / kChunkElems;
+    e.full_chunks = (unsigned)full;
+    e.tail_elems = (unsigned)(n - full * kChunkElems);
+    e.tail_bytes = (unsigned)(packed_bytes_of(n) - full * kChunkQuads);
+    e.pad_ = 0;
+    return e;
+}
+
+constexpr unsigned long long kMaxGrid = 0x7FFFFFFFull;
+
+// A threshold 2^e (moderate e): every multiple m*t, |m| <= 2*CDSGD_MAX_WORKERS, is exact.
+inline bool is_pow2_threshold(float t)
+{
+    int e = 0;
+    const float m = std::frexp(t, &e);
+    return m == 0.5f && e > -100 && e < 100;
+}
+
+inline bool good_threshold(float t) { return std::isfinite(t) && t > 0.0f; }
+
+inline int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? CDSGD_OK : CDSGD_ERR_DEVICE;
+}
+
+}  // namespace
+
+struct cdsgd_plan {
+    void *device_block = nullptr;  // one allocation: tensors, chunks, peer pointers
+    TensorDesc *tensors = nullptr;
+    ChunkRef *chunks = nullptr;
+    const uint8_t **peers = nullptr;
+    int num_tensors = 0;
+    int num_workers = 0;
+    int self = 0;
+    unsigned num_chunks = 0;
+    bool has_agg_full = false;
+};
+
+extern "C" {
+
+size_t cdsgd_packed_words(size_t n) { return (n + 15) / 16; }
+
+const char *cdsgd_status_string(int status)
+{
+    switch (status) {
+    case CDSGD_OK: return "ok";
+    case CDSGD_ERR_NULL: return "a required pointer is NULL";
+    case CDSGD_ERR_SIZE: return "bad size (zero elements, no tensors, or too large for one launch)";
+    case CDSGD_ERR_PARAM: return "bad parameter (threshold, k, step or learning rate)";
+    case CDSGD_ERR_ALIGN: return "pointer not aligned (fp32 buffers 16 bytes, packed buffers 4 bytes)";
+    case CDSGD_ERR_WORKERS: return "bad worker count or worker index";
+    case CDSGD_ERR_DEVICE: return "a HIP call failed";
+    default: return "unknown status";
+    }
+}
+
+int cdsgd_quantize_pack(const float *grad, float *residual, uint32_t *packed, size_t n, float threshold,
+                        void *hip_stream)
+{
+    if (!grad || !residual || !packed) return CDSGD_ERR_NULL;
+    if (n == 0 || chunks_of(n) > kMaxGrid) return CDSGD_ERR_SIZE;
+    if (!good_threshold(threshold)) return CDSGD_ERR_PARAM;
+    if (!aligned(grad, 16) || !aligned(residual, 16) || !aligned(packed, 4)) return CDSGD_ERR_ALIGN;
+    const unsigned grid = (unsigned)chunks_of(n);
+    hipLaunchKernelGGL(k_quantize_pack, dim3(grid), dim3(kBlock), 0, (hipStream_t)hip_stream, grad, residual,
+                       reinterpret_cast<uint8_t *>(packed), extent_of(n), threshold);
+    return launch_status();
+}
+
+int cdsgd_decode_sum(const uint32_t *const *packed, int num_workers, float *agg, size_t n, float threshold,
+                     void *hip_stream)
+{
+    if (!packed || !agg) return CDSGD_ERR_NULL;
+    if (n == 0 || chunks_of(n) > kMaxGrid) return CDSGD_ERR_SIZE;
+    if (!good_threshold(threshold)) return CDSGD_ERR_PARAM;
+    if (num_workers < 1 || num_workers > CDSGD_MAX_WORKERS) return CDSGD_ERR_WORKERS;
+    for (int j = 0; j < num_workers; ++j)
+        if (!packed[j]) return CDSGD_ERR_NULL;
+    if (!aligned(agg, 16)) return CDSGD_ERR_ALIGN;
+    for (int j = 0; j < num_workers; ++j)
+        if (!aligned(packed[j], 4)) return CDSGD_ERR_ALIGN;
+    StreamTable tab;
+    std::memset(&tab, 0, sizeof(tab));
+    for (int j = 0; j < num_workers; ++j) tab.p[j] = reinterpret_cast<const uint8_t *>(packed[j]);
+    const unsigned grid = (unsigned)chunks_of(n);
+    const float bias_t = -(2.0f * (float)num_workers) * threshold;
+    if (is_pow2_threshold(threshold))
+        hipLaunchKernelGGL(k_decode_sum<true>, dim3(grid), dim3(kBlock), 0, (hipStream_t)hip_stream, tab,
+                           num_workers, agg, extent_of(n), threshold, bias_t);
+    else
+        hipLaunchKernelGGL(k_decode_sum<false>, dim3(grid), dim3(kBlock), 0, (hipStream_t)hip_stream, tab,
+                           num_workers, agg, extent_of(n), threshold, bias_t);
+    return launch_status();
+}
+
+int cdsgd_update(float *w_global, float *w_local, const float *grad_local, const float *agg, size_t n,
+                 float lr_local, float lr_global, int num_workers, void *hip_stream)
+{
+    const bool local = w_local != nullptr || grad_local != nullptr;
+    const bool global = agg != nullptr;
+    if (!w_global) return CDSGD_ERR_NULL;
+    if (local && (!w_local || !grad_local)) return CDSGD_ERR_NULL;
+    if (!local && !global) return CDSGD_ERR_NULL;
+    if (n == 0 || chunks_of(n) > kMaxGrid) return CDSGD_ERR_SIZE;
+    if (!std::isfinite(lr_local) || !std::isfinite(lr_global)) return CDSGD_ERR_PARAM;
+    if (num_workers < 1 || num_workers > CDSGD_MAX_WORKERS) return CDSGD_ERR_WORKERS;
+    if (!aligned(w_global, 16) || !aligned(w_local, 16) || !aligned(grad_local, 16) || !aligned(agg, 16))
+        return CDSGD_ERR_ALIGN;
+    const unsigned grid = (unsigned)chunks_of(n);
+    const float scale = lr_global / (float)num_workers;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const Extent nn = extent_of(n);
+    if (local && global)
+        hipLaunchKernelGGL((k_update<true, true>), dim3(grid), dim3(kBlock), 0, s, w_global, w_local, grad_local, agg, nn, lr_local, scale);
+    else if (local)
+        hipLaunchKernelGGL((k_update<true, false>), dim3(grid), dim3(kBlock), 0, s, w_global, w_local, grad_local, agg, nn, lr_local, scale);
+    else
+        hipLaunchKernelGGL((k_update<false, true>), dim3(grid), dim3(kBlock), 0, s, w_global, w_local, grad_local, agg, nn, lr_local, scale);
+    return launch_status();
+}
+
+int cdsgd_plan_create(const cdsgd_tensor *tensors, int num_tensors, const uint32_t *const *const *peers,
+                      int num_workers, int self, cdsgd_plan **out)
+{
+    if (!out) return CDSGD_ERR_NULL;
+    *out = nullptr;
+    if (!tensors) return CDSGD_ERR_NULL;
+    if (num_tensors < 1) return CDSGD_ERR_SIZE;
+    if (num_workers < 1 || num_workers > CDSGD_MAX_WORKERS || self < 0 || self >= num_workers)
+        return CDSGD_ERR_WORKERS;
+    if (num_workers > 1 && !peers) return CDSGD_ERR_NULL;
+    unsigned long long total_chunks = 0;
+    bool all_agg = true;
+    for (int i = 0; i < num_tensors; ++i) {
+        const cdsgd_tensor &t = tensors[i];
+        if (!t.w_global || !t.w_local || !t.residual || !t.grad || !t.packed_self) return CDSGD_ERR_NULL;
+        if (t.n == 0 || chunks_of(t.n) > kMaxGrid) return CDSGD_ERR_SIZE;
+        if (!aligned(t.w_global, 16) || !aligned(t.w_local, 16) || !aligned(t.residual, 16) ||
+            !aligned(t.grad, 16) || !aligned(t.agg_full, 16) || !aligned(t.packed_self, 4))
+            return CDSGD_ERR_ALIGN;
+        all_agg = all_agg && t.agg_full != nullptr;
+        total_chunks += chunks_of(t.n);
+        if (total_chunks > kMaxGrid) return CDSGD_ERR_SIZE;
+    }
+    const int num_peers = num_workers - 1;
+    for (int j = 0; j < num_workers; ++j) {
+        if (j == self) continue;
+        if (!peers[j]) return CDSGD_ERR_NULL;
+        for (int i = 0; i < num_tensors; ++i) {
+            if (!peers[j][i]) return CDSGD_ERR_NULL;
+            if (!aligned(peers[j][i], 4)) return CDSGD_ERR_ALIGN;
+        }
+    }
+
+    // host image of the device block
+    const size_t bytes_t = sizeof(TensorDesc) * (size_t)num_tensors;
+    const size_t bytes_c = sizeof(ChunkRef) * (size_t)total_chunks;
+    const size_t bytes_p = sizeof(const uint8_t *) * (size_t)num_tensors * (size_t)(num_peers > 0 ? num_peers : 1);
+    const size_t off_c = (bytes_t + 255) & ~(size_t)255;
+    const size_t off_p = (off_c + bytes_c + 255) & ~(size_t)255;
+    const size_t total = off_p + bytes_p;
+    std::vector<unsigned char> image(total, 0);
+    TensorDesc *ht = reinterpret_cast<TensorDesc *>(image.data());
+    ChunkRef *hc = reinterpret_cast<ChunkRef *>(image.data() + off_c);
+    const uint8_t **hp = reinterpret_cast<const uint8_t **>(image.data() + off_p);
+    size_t ci = 0;
+    for (int i = 0; i < num_tensors; ++i) {
+        const cdsgd_tensor &t = tensors[i];
+        ht[i].w_global = t.w_global;
+        ht[i].w_local = t.w_local;
+        ht[i].residual = t.residual;
+        ht[i].grad = t.grad;
+        ht[i].packed_self = reinterpret_cast<uint8_t *>(t.packed_self);
+        ht[i].agg_full = t.agg_full;
+        ht[i].ext = extent_of(t.n);
+        const unsigned nc = (unsigned)chunks_of(t.n);
+        for (unsigned c = 0; c < nc; ++c) {
+            hc[ci].tensor = (unsigned)i;
+            hc[ci].chunk = c;
+            ++ci;
+        }
+        int slot = 0;
+        for (int j = 0; j < num_workers; ++j) {
+            if (j == self) continue;
+            hp[(size_t)i * (size_t)num_peers + (size_t)slot] = reinterpret_cast<const uint8_t *>(peers[j][i]);
+            ++slot;
+        }
+    }
+
+    cdsgd_plan *plan = new (std::nothrow) cdsgd_plan;
+    if (!plan) return CDSGD_ERR_DEVICE;
+    if (hipMalloc(&plan->device_block, total) != hipSuccess) {
+        (void)hipGetLastError();
+        delete plan;
+        return CDSGD_ERR_DEVICE;
+    }
+    if (hipMemcpy(plan->device_block, image.data(), total, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipFree(plan->device_block);
+        delete plan;
+        return CDSGD_ERR_DEVICE;
+    }
+    unsigned char *base = static_cast<unsigned char *>(plan->device_block);
+    plan->tensors = reinterpret_cast<TensorDesc *>(base);
+    plan->chunks = reinterpret_cast<ChunkRef *>(base + off_c);
+    plan->peers = reinterpret_cast<const uint8_t **>(base + off_p);
+    plan->num_tensors = num_tensors;
+    plan->num_workers = num_workers;
+    plan->self = self;
+    plan->num_chunks = (unsigned)total_chunks;
+    plan->has_agg_full = all_agg;
+    *out = plan;
+    return CDSGD_OK;
+}
+
+int cdsgd_plan_destroy(cdsgd_plan *plan)
+{
+    if (!plan) return CDSGD_OK;
+    int rc = CDSGD_OK;
+    if (plan->device_block && hipFree(plan->device_block) != hipSuccess) {
+        (void)hipGetLastError();
+        rc = CDSGD_ERR_DEVICE;
+    }
+    delete plan;
+    return rc;
+}
+
+int cdsgd_step_fused(cdsgd_plan *plan, long step, int k, float threshold, float lr_local, float lr_global,
+                     void *hip_stream)
+{
+    if (!plan) return CDSGD_ERR_NULL;
+    if (k < 1 || step < 0 || !good_threshold(threshold) || !std::isfinite(lr_local) || !std::isfinite(lr_global))
+        return CDSGD_ERR_PARAM;
+    const bool compressed = (step % k) != 0;
+    if (!compressed && !plan->has_agg_full) return CDSGD_ERR_NULL;
+    const float scale = lr_global / (float)plan->num_workers;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const dim3 grid(plan->num_chunks), block(kBlock);
+    if (compressed) {
+        const int num_peers = plan->num_workers - 1;
+        const float bias_t = -(2.0f * (float)plan->num_workers) * threshold;
+        if (is_pow2_threshold(threshold))
+            hipLaunchKernelGGL(k_fused_compressed<true>, grid, block, 0, s, plan->tensors, plan->chunks,
+                               plan->peers, num_peers, plan->self, threshold, lr_local, scale, bias_t);
+        else
+            hipLaunchKernelGGL(k_fused_compressed<false>, grid, block, 0, s, plan->tensors, plan->chunks,
+                               plan->peers, num_peers, plan->self, threshold, lr_local, scale, bias_t);
+    } else {
+        hipLaunchKernelGGL(k_fused_correction, grid, block, 0, s, plan->tensors, plan->chunks, lr_local, scale);
+    }
+    return launch_status();
+}
+
+}  // extern "C"

@@ -1,0 +1,165 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol the header declares, and turns bad arguments into status codes before any
+HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "cdsgd.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2106_10796_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    return binding.lib()
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(cdsgd_[a-z_]+)\s*\(", src)))
+
+
+def test_header_declares_the_named_entry_points():
+    names = declared_functions()
+    for must in ("cdsgd_quantize_pack", "cdsgd_decode_sum", "cdsgd_update", "cdsgd_step_fused",
+                 "cdsgd_plan_create", "cdsgd_plan_destroy", "cdsgd_packed_words", "cdsgd_status_string"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol(L):
+    for name in declared_functions():
+        assert hasattr(L, name), name
+
+
+def test_packed_words(L):
+    for n, w in ((1, 1), (15, 1), (16, 1), (17, 2), (32, 2), (33, 3), (65536, 4096), (1 << 30, 1 << 26)):
+        assert L.cdsgd_packed_words(n) == w
+
+
+def test_status_strings(L):
+    seen = set()
+    for s in range(7):
+        msg = L.cdsgd_status_string(s)
+        assert msg and msg not in seen
+        seen.add(msg)
+    assert L.cdsgd_status_string(99) == b"unknown status"
+
+
+A = 0x1000  # a fake, well aligned, non-NULL device address; never dereferenced on these paths
+
+
+def test_quantize_pack_argument_errors(L):
+    from paper_2106_10796_amd.binding import ERR_ALIGN, ERR_NULL, ERR_PARAM, ERR_SIZE
+    q = L.cdsgd_quantize_pack
+    assert q(None, A, A, 16, 0.5, None) == ERR_NULL
+    assert q(A, None, A, 16, 0.5, None) == ERR_NULL
+    assert q(A, A, None, 16, 0.5, None) == ERR_NULL
+    assert q(A, A, A, 0, 0.5, None) == ERR_SIZE
+    for t in (0.0, -0.5, float("nan"), float("inf")):
+        assert q(A, A, A, 16, t, None) == ERR_PARAM
+    assert q(A + 4, A, A, 16, 0.5, None) == ERR_ALIGN
+    assert q(A, A + 8, A, 16, 0.5, None) == ERR_ALIGN
+    assert q(A, A, A + 2, 16, 0.5, None) == ERR_ALIGN
+
+
+def test_decode_sum_argument_errors(L):
+    from paper_2106_10796_amd.binding import ERR_ALIGN, ERR_NULL, ERR_PARAM, ERR_SIZE, ERR_WORKERS, MAX_WORKERS
+    d = L.cdsgd_decode_sum
+    two = (ctypes.c_void_p * 2)(A, A)
+    assert d(None, 2, A, 16, 0.5, None) == ERR_NULL
+    assert d(two, 2, None, 16, 0.5, None) == ERR_NULL
+    assert d(two, 2, A, 0, 0.5, None) == ERR_SIZE
+    assert d(two, 2, A, 16, -1.0, None) == ERR_PARAM
+    assert d(two, 0, A, 16, 0.5, None) == ERR_WORKERS
+    many = (ctypes.c_void_p * (MAX_WORKERS + 1))(*([A] * (MAX_WORKERS + 1)))
+    assert d(many, MAX_WORKERS + 1, A, 16, 0.5, None) == ERR_WORKERS
+    hole = (ctypes.c_void_p * 2)(A, None)
+    assert d(hole, 2, A, 16, 0.5, None) == ERR_NULL
+    assert d(two, 2, A + 4, 16, 0.5, None) == ERR_ALIGN
+    odd = (ctypes.c_void_p * 2)(A, A + 1)
+    assert d(odd, 2, A, 16, 0.5, None) == ERR_ALIGN
+
+
+def test_update_argument_errors(L):
+    from paper_2106_10796_amd.binding import ERR_ALIGN, ERR_NULL, ERR_PARAM, ERR_SIZE, ERR_WORKERS
+    u = L.cdsgd_update
+    assert u(None, A, A, A, 16, 0.1, 0.1, 2, None) == ERR_NULL
+    assert u(A, A, None, A, 16, 0.1, 0.1, 2, None) == ERR_NULL   # local half given without gradient
+    assert u(A, None, A, A, 16, 0.1, 0.1, 2, None) == ERR_NULL
+    assert u(A, None, None, None, 16, 0.1, 0.1, 2, None) == ERR_NULL  # nothing to do
+    assert u(A, A, A, A, 0, 0.1, 0.1, 2, None) == ERR_SIZE
+    assert u(A, A, A, A, 16, float("nan"), 0.1, 2, None) == ERR_PARAM
+    assert u(A, A, A, A, 16, 0.1, float("inf"), 2, None) == ERR_PARAM
+    assert u(A, A, A, A, 16, 0.1, 0.1, 0, None) == ERR_WORKERS
+    assert u(A, A, A, A, 16, 0.1, 0.1, 65, None) == ERR_WORKERS
+    assert u(A, A + 4, A, A, 16, 0.1, 0.1, 2, None) == ERR_ALIGN
+
+
+def _tensor(L, **kw):
+    from paper_2106_10796_amd.binding import cdsgd_tensor
+    t = cdsgd_tensor()
+    t.w_global = t.w_local = t.residual = t.grad = t.packed_self = t.agg_full = A
+    t.n = 64
+    for k, v in kw.items():
+        setattr(t, k, v)
+    return t
+
+
+def test_plan_and_step_argument_errors(L):
+    from paper_2106_10796_amd.binding import (ERR_ALIGN, ERR_NULL, ERR_PARAM, ERR_SIZE, ERR_WORKERS, OK,
+                                              cdsgd_tensor)
+    create = L.cdsgd_plan_create
+    out = ctypes.c_void_p()
+    arr = (cdsgd_tensor * 1)(_tensor(L))
+    row = (ctypes.c_void_p * 1)(A)
+    rows = (ctypes.POINTER(ctypes.c_void_p) * 2)(ctypes.POINTER(ctypes.c_void_p)(),
+                                                 ctypes.cast(row, ctypes.POINTER(ctypes.c_void_p)))
+    assert create(arr, 1, rows, 2, 0, None) == ERR_NULL
+    assert create(None, 1, rows, 2, 0, ctypes.byref(out)) == ERR_NULL
+    assert create(arr, 0, rows, 2, 0, ctypes.byref(out)) == ERR_SIZE
+    assert create(arr, 1, rows, 0, 0, ctypes.byref(out)) == ERR_WORKERS
+    assert create(arr, 1, rows, 2, 2, ctypes.byref(out)) == ERR_WORKERS
+    assert create(arr, 1, rows, 2, -1, ctypes.byref(out)) == ERR_WORKERS
+    assert create(arr, 1, None, 2, 0, ctypes.byref(out)) == ERR_NULL        # peers needed for N > 1
+    assert create(arr, 1, rows, 2, 1, ctypes.byref(out)) == ERR_NULL        # row 0 is a peer now and is NULL
+    for fld in ("w_global", "w_local", "residual", "grad", "packed_self"):
+        bad = (cdsgd_tensor * 1)(_tensor(L, **{fld: None}))
+        assert create(bad, 1, rows, 2, 0, ctypes.byref(out)) == ERR_NULL
+    assert create((cdsgd_tensor * 1)(_tensor(L, n=0)), 1, rows, 2, 0, ctypes.byref(out)) == ERR_SIZE
+    assert create((cdsgd_tensor * 1)(_tensor(L, grad=A + 4)), 1, rows, 2, 0, ctypes.byref(out)) == ERR_ALIGN
+    badrow = (ctypes.c_void_p * 1)(A + 2)
+    badrows = (ctypes.POINTER(ctypes.c_void_p) * 2)(ctypes.POINTER(ctypes.c_void_p)(),
+                                                    ctypes.cast(badrow, ctypes.POINTER(ctypes.c_void_p)))
+    assert create(arr, 1, badrows, 2, 0, ctypes.byref(out)) == ERR_ALIGN
+    assert out.value is None
+    step = L.cdsgd_step_fused
+    assert step(None, 1, 4, 0.5, 0.1, 0.1, None) == ERR_NULL
+    assert L.cdsgd_plan_destroy(None) == OK
+    fake = ctypes.c_void_p(A)  # parameter checks come before the plan is looked at
+    assert step(fake, 1, 0, 0.5, 0.1, 0.1, None) == ERR_PARAM
+    assert step(fake, -1, 4, 0.5, 0.1, 0.1, None) == ERR_PARAM
+    assert step(fake, 1, 4, 0.0, 0.1, 0.1, None) == ERR_PARAM
+    assert step(fake, 1, 4, 0.5, float("nan"), 0.1, None) == ERR_PARAM
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    from paper_2106_10796_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        binding.lib()
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2106_10796_amd")
+    pat = re.compile(r"^\s*(from\s+oracle|import\s+oracle|from\s+\.+\s*oracle)|liboracle|cdsgd_oracle", re.M)
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                assert not pat.search(open(os.path.join(dirpath, f)).read()), f

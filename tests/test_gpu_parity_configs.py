@@ -1,0 +1,204 @@
+"""GPU parity on the five workloads, in the launch configuration the benchmark times.
+
+Small workloads (single tensor, ResNet-20-shaped list) are compared whole, every step,
+fused and three-call path, literal and dense value recipes.  The large ones (ResNet-50,
+VGG-16, 4 GiB flat bucket) run at full size and are compared on sampled blocks that the
+oracle can recompute one by one (first / last / ragged-tail / random blocks; the path is
+elementwise, so a block of outputs depends only on the same block of inputs), plus, over
+the whole buffers, fused == three-call path bit for bit and the conservation property of
+the quantiser.
+"""
+import numpy as np
+import pytest
+import torch
+
+from helpers import assert_bits_equal, assert_close, count_bit_equal
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2106_10796_amd as pkg
+    from paper_2106_10796_amd import runner, synth
+    pkg.binding.lib()
+    assert torch.cuda.is_available()
+    return pkg, runner, synth
+
+
+def _whole(cfg):
+    return [(i, 0, n) for i, n in enumerate(cfg.sizes)]
+
+
+def _sample_blocks(cfg, rng, nblocks, blen):
+    """(tensor, start, length): starts are multiples of 16; blocks either end on a multiple
+    of 16 or at the tensor's (possibly ragged) end."""
+    out = []
+    order = np.argsort(cfg.sizes)[::-1]
+    big = int(order[0])
+    n = cfg.sizes[big]
+    out.append((big, 0, min(blen, n)))                                   # first block
+    out.append((big, max(0, (n - blen) // 16 * 16), n - max(0, (n - blen) // 16 * 16)))  # last block
+    ragged = [i for i, m in enumerate(cfg.sizes) if m % 16]
+    for i in ragged[:4]:                                                 # ragged tails
+        m = cfg.sizes[i]
+        s = max(0, (m - 2048) // 16 * 16)
+        out.append((i, s, m - s))
+    small = [i for i in order[::-1][:3]]                                 # smallest tensors, whole
+    for i in small:
+        out.append((int(i), 0, min(cfg.sizes[i], blen)))
+    while len(out) < nblocks:
+        i = int(rng.choice(len(cfg.sizes), p=np.array(cfg.sizes) / sum(cfg.sizes)))
+        m = cfg.sizes[i]
+        ln = min(blen, m)
+        s = int(rng.integers(0, (m - ln) // 16 + 1)) * 16
+        out.append((i, s, min(ln, m - s)))
+    return out
+
+
+def _run(P, oracle, cfg, dense, steps, blocks, fused=True, self_rank=0, check_peers=True, shadow=False):
+    """Steps the workload on the GPU and the oracle on the blocks; compares after every step.
+
+    shadow=True keeps a second copy of the observed worker's state that is stepped with the
+    three single-tensor calls, and requires whole-arena bit equality with the fused state."""
+    pkg, runner, synth = P
+    wl = runner.Workload(cfg, dense=dense, self_rank=self_rank)
+    sh = None
+    if shadow:
+        sh = dict(w_global=wl.w_global.clone(), w_local=wl.w_local.clone(), residual=wl.residual.clone(),
+                  packed_self=wl.packed_self.clone())
+    N, t = cfg.num_workers, cfg.threshold
+    sims = [oracle.Simulation(wl.view(wl.w_global, i)[a: a + ln].cpu().numpy(), N, cfg.k, t, cfg.lr, cfg.lr,
+                              self_rank) for (i, a, ln) in blocks]
+    nonzero_codes = 0
+    total_codes = 0
+    bit_equal = [0, 0]
+    for s in range(steps):
+        cap = wl.prepare_step(s, capture=blocks)
+        comp = wl.compressed(s)
+        r_old = wl.residual.clone() if (comp and shadow) else None
+        if fused:
+            wl.fused_step(s)
+        else:
+            wl.unfused_step(s)
+        torch.cuda.synchronize()
+        if shadow:
+            # three-call path on the copy, then swap back
+            live = dict(w_global=wl.w_global, w_local=wl.w_local, residual=wl.residual, packed_self=wl.packed_self)
+            for key in sh:
+                setattr(wl, key, sh[key])
+            wl.unfused_step(s)
+            torch.cuda.synchronize()
+            for key in sh:
+                setattr(wl, key, live[key])
+                assert torch.equal(live[key].view(torch.int32), sh[key].view(torch.int32)), \
+                    "fused vs three-call path differ in %s at step %d" % (key, s)
+            if comp:
+                # conservation over the whole arena: (r_old + g) - value(code) == r_new, in fp32
+                by = wl.packed_self.view(torch.uint8)
+                a = r_old + wl.grad
+                for c4 in range(4):
+                    code = (by >> (2 * c4)) & 3
+                    assert int((code == 3).sum()) == 0
+                    val = torch.where(code == 1, t, 0.0) - torch.where(code == 2, t, 0.0)
+                    ok = torch.equal((a[c4::4] - val.to(torch.float32)).view(torch.int32),
+                                     wl.residual[c4::4].view(torch.int32))
+                    assert ok, "conservation broken at step %d" % s
+        for b, (i, a, ln) in enumerate(blocks):
+            grads = [np.ascontiguousarray(cap[j][b]) for j in range(N)]
+            c, agg, words = sims[b].step(grads)
+            assert c == comp
+            tag = "%s step %d block %d (tensor %d, start %d, len %d)" % (cfg.name, s, b, i, a, ln)
+            sl = slice(a, a + ln)
+            wsl = slice(a // 16, a // 16 + (ln + 15) // 16)
+            if comp:
+                got = wl.pview(wl.packed_self, i)[wsl].cpu().numpy()
+                assert_bits_equal(got, words[self_rank].view(np.int32), "packed_self " + tag)
+                assert_bits_equal(wl.view(wl.residual, i)[sl].cpu().numpy(), sims[b].residual[self_rank],
+                                  "residual " + tag)
+                codes = oracle.unpack(words[self_rank], ln)
+                nonzero_codes += int((codes != 0).sum())
+                total_codes += ln
+                if check_peers:
+                    for j in range(N):
+                        if j == self_rank:
+                            continue
+                        assert_bits_equal(wl.pview(wl.peer_packed[j], i)[wsl].cpu().numpy(),
+                                          words[j].view(np.int32), "peer %d packed " % j + tag)
+                        assert_bits_equal(wl.view(wl.peer_residual[j], i)[sl].cpu().numpy(),
+                                          sims[b].residual[j], "peer %d residual " % j + tag)
+            else:
+                assert_bits_equal(wl.view(wl.agg_full, i)[sl].cpu().numpy(), agg, "agg_full " + tag)
+                assert_bits_equal(wl.view(wl.residual, i)[sl].cpu().numpy(), sims[b].residual[self_rank],
+                                  "residual (correction) " + tag)
+            gw = wl.view(wl.w_global, i)[sl].cpu().numpy()
+            gl = wl.view(wl.w_local, i)[sl].cpu().numpy()
+            assert_close(gw, sims[b].w_global, "w_global " + tag)
+            assert_close(gl, sims[b].w_local, "w_local " + tag)
+            for got, want in ((gw, sims[b].w_global), (gl, sims[b].w_local)):
+                e, n = count_bit_equal(got, want)
+                bit_equal[0] += e
+                bit_equal[1] += n
+    wl.destroy()
+    # both sides use the same single-rounding form, so bit equality is the expected outcome
+    assert bit_equal[0] == bit_equal[1], "weights within 1e-6 but only %d of %d bit-equal" % tuple(bit_equal)
+    return nonzero_codes, total_codes
+
+
+@pytest.mark.parametrize("fused", [True, False], ids=["fused", "threecall"])
+@pytest.mark.parametrize("dense", [False, True], ids=["literal", "dense"])
+def test_c1_single_tensor_whole_run(P, oracle, dense, fused):
+    cfg = P[2].config("c1_single")
+    nz, tot = _run(P, oracle, cfg, dense, cfg.iterations, _whole(cfg), fused=fused)
+    assert tot == 6 * 65536                 # 6 of the 8 iterations are compressed (k = 4)
+    assert nz > (0.2 * tot if dense else 0)  # the literal recipe fires a little, the dense one a lot
+
+
+@pytest.mark.parametrize("fused", [True, False], ids=["fused", "threecall"])
+@pytest.mark.parametrize("dense", [False, True], ids=["literal", "dense"])
+def test_c2_resnet20_whole_run(P, oracle, dense, fused):
+    cfg = P[2].config("c2_resnet20")
+    nz, tot = _run(P, oracle, cfg, dense, cfg.iterations, _whole(cfg), fused=fused)
+    assert tot == 15 * cfg.elements
+    if dense:
+        assert nz > 0.2 * tot
+
+
+def test_c2_other_worker_positions(P, oracle):
+    cfg = P[2].config("c2_resnet20")
+    for self_rank in (3, 7):
+        _run(P, oracle, cfg, True, 6, _whole(cfg), fused=True, self_rank=self_rank)
+
+
+@pytest.mark.parametrize("dense", [False, True], ids=["literal", "dense"])
+def test_c3_resnet50_full_size_sampled(P, oracle, dense):
+    cfg = P[2].config("c3_resnet50")
+    rng = np.random.default_rng(33)
+    blocks = _sample_blocks(cfg, rng, 24, 1 << 13)
+    nz, tot = _run(P, oracle, cfg, dense, 10, blocks, shadow=True)
+    if dense:
+        assert nz > 0.2 * tot
+
+
+@pytest.mark.parametrize("dense", [False, True], ids=["literal", "dense"])
+def test_c4_vgg16_full_size_sampled(P, oracle, dense):
+    cfg = P[2].config("c4_vgg16")
+    rng = np.random.default_rng(44)
+    blocks = _sample_blocks(cfg, rng, 20, 1 << 13)
+    nz, tot = _run(P, oracle, cfg, dense, 4 if not dense else 3, blocks, shadow=True)
+    if dense:
+        assert nz > 0.2 * tot
+
+
+def test_c5_flat_bucket_full_size_sampled(P, oracle):
+    """4 GiB bucket, t = 0.05 (not a power of two: the literal fp32 chain is what runs)."""
+    cfg = P[2].config("c5_flat4g")
+    rng = np.random.default_rng(55)
+    n = cfg.sizes[0]
+    blocks = [(0, 0, 1 << 14), (0, n - (1 << 14), 1 << 14), (0, (1 << 29) - 4096, 8192),   # around 2 GiB
+              (0, (1 << 28) * 3 - 4096, 8192)]
+    for _ in range(12):
+        blocks.append((0, int(rng.integers(0, n // 16 - 1024)) * 16, 1 << 13))
+    nz, tot = _run(P, oracle, cfg, False, 3, blocks, shadow=True)
+    # first compressed step fires with probability exp(-2.5); later ones a little more
+    assert 0.05 * tot < nz < 0.25 * tot

@@ -1,0 +1,222 @@
+"""GPU parity, entry point by entry point: HIP library (through the C ABI) vs the CPU oracle,
+element by element on the same seeded inputs.  Sizes span several chunks (4096 elements),
+several waves, and every kind of ragged tail.  Packed words and residuals: bit-exact.
+Aggregate and weights: within 1e-6 relative (bit equality is also counted and required
+where both sides use the same single-rounding form)."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import assert_bits_equal, assert_close
+
+pytestmark = pytest.mark.gpu
+
+SIZES = [1, 2, 3, 4, 5, 15, 16, 17, 31, 33, 63, 64, 65, 255, 1023, 1024, 1025, 4093, 4095, 4096,
+         4097, 4111, 8191, 12289, 16384, 65536, 100003]
+GUARD = 64  # sentinel elements on both sides of every output buffer
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2106_10796_amd import binding
+    binding.lib()
+    assert torch.cuda.is_available()
+    return binding
+
+
+def guarded(n, dtype, fill):
+    """A device buffer with sentinels around an aligned interior view."""
+    full = torch.full((n + 2 * GUARD,), fill, dtype=dtype, device="cuda")
+    return full, full[GUARD: GUARD + n]
+
+
+def guards_intact(full, n, fill):
+    f = full.cpu()
+    return bool((f[:GUARD] == fill).all() and (f[GUARD + n:] == fill).all())
+
+
+def rand_inputs(rng, n, t):
+    g = (rng.normal(0, 1.2 * t, n)).astype(np.float32)
+    r = rng.uniform(-t, t, n).astype(np.float32)
+    # force exact-threshold cases in
+    if n >= 4:
+        r[0], g[0] = 0.0, t
+        r[1], g[1] = 0.0, -t
+        r[2], g[2] = np.float32(t) / 2, np.float32(t) / 2
+        r[3], g[3] = 0.0, np.nextafter(np.float32(t), np.float32(0))
+    return g, r
+
+
+@pytest.mark.parametrize("t", [0.5, 0.05])
+@pytest.mark.parametrize("n", SIZES)
+def test_quantize_pack(B, oracle, n, t):
+    rng = np.random.default_rng(1000 + n)
+    g, r = rand_inputs(rng, n, t)
+    nw = B.packed_words(n)
+    dg = torch.from_numpy(g).cuda()
+    rfull, dr = guarded(n, torch.float32, 7.0)
+    dr.copy_(torch.from_numpy(r))
+    pfull, dp = guarded(nw, torch.int32, -1)     # stale 0xFFFFFFFF: pad bits must be cleared
+    B.cdsgd_quantize_pack(dg, dr, dp, t)
+    torch.cuda.synchronize()
+    r_o = r.copy()
+    words = oracle.quantize_pack(g, r_o, t)
+    assert_bits_equal(dp.cpu().numpy(), words.view(np.int32), "packed n=%d" % n)
+    assert_bits_equal(dr.cpu().numpy(), r_o, "residual n=%d" % n)
+    assert guards_intact(rfull, n, 7.0) and guards_intact(pfull, nw, -1)
+    assert_bits_equal(dg.cpu().numpy(), g, "grad must not be written")
+
+
+def test_quantize_pack_special_values(B, oracle):
+    den = np.float32(1e-45)
+    g = np.array([np.nan, np.inf, -np.inf, den, -den, 0.0, -0.0, 3e-39, 1e30, -1e30], np.float32)
+    r = np.array([0, 0, 0, den, 0, 0, -0.0, 3e-39, 1e30, 0.25], np.float32)
+    dg, dr = torch.from_numpy(g).cuda(), torch.from_numpy(r).cuda()
+    dp = B.new_packed(g.size)
+    B.cdsgd_quantize_pack(dg, dr, dp, 0.5)
+    r_o = r.copy()
+    words = oracle.quantize_pack(g, r_o, 0.5)
+    assert_bits_equal(dp.cpu().numpy(), words.view(np.int32), "packed")
+    assert_bits_equal(dr.cpu().numpy(), r_o, "residual (NaN matches NaN)")
+    out = dr.cpu().numpy()
+    assert out[3] == np.float32(3e-45) and out[7] != 0.0   # denormals survive, no flush
+
+
+@pytest.mark.parametrize("t", [0.5, 0.05, 0.3, 2.0 ** -20])
+@pytest.mark.parametrize("N", [1, 2, 3, 4, 5, 8, 9, 12, 13, 16, 17, 33, 64])
+def test_decode_sum(B, oracle, N, t):
+    rng = np.random.default_rng(2000 + N)
+    for n in (1, 17, 4095, 4097, 20000):
+        nw = B.packed_words(n)
+        # codes with a bias towards one sign so that sums run up, the unused code 3 included,
+        # and random garbage in the pad bits of the last word (must not matter)
+        codes = rng.choice(4, size=(N, n), p=[0.3, 0.4, 0.25, 0.05]).astype(np.uint8)
+        words = [oracle.pack(np.ascontiguousarray(codes[j])) for j in range(N)]
+        if n % 16:
+            for w in words:
+                w[-1] |= np.uint32(rng.integers(0, 1 << 32) & ~((1 << (2 * (n % 16))) - 1) & 0xFFFFFFFF)
+        dw = [torch.from_numpy(w.view(np.int32)).cuda() for w in words]
+        afull, da = guarded(n, torch.float32, 9.0)
+        B.cdsgd_decode_sum(dw, da, t)
+        torch.cuda.synchronize()
+        agg = oracle.decode_sum(words, n, t)
+        assert_close(da.cpu().numpy(), agg, "agg N=%d n=%d t=%g" % (N, n, t))
+        assert_bits_equal(da.cpu().numpy(), agg, "agg bits N=%d n=%d t=%g" % (N, n, t))
+        assert guards_intact(afull, n, 9.0)
+
+
+@pytest.mark.parametrize("n", [1, 3, 4, 5, 1023, 4096, 4099, 70001])
+@pytest.mark.parametrize("mode", ["both", "local", "global"])
+def test_update(B, oracle, n, mode):
+    rng = np.random.default_rng(3000 + n)
+    W = rng.normal(0, 1, n).astype(np.float32)
+    g = rng.normal(0, 1, n).astype(np.float32)
+    agg = (rng.integers(-16, 17, n) * 0.5).astype(np.float32)
+    N, lr_l, lr_g = 3, 0.4, 0.1
+    wfull, dW = guarded(n, torch.float32, 5.0)
+    dW.copy_(torch.from_numpy(W))
+    lfull, dL = guarded(n, torch.float32, 6.0)
+    dg, da = torch.from_numpy(g).cuda(), torch.from_numpy(agg).cuda()
+    W_o, L_o = W.copy(), np.full(n, 6.0, np.float32)
+    if mode == "both":
+        B.cdsgd_update(dW, dL, dg, da, lr_l, lr_g, N)
+        oracle.update(W_o, L_o, g, agg, lr_l, lr_g, N)
+    elif mode == "local":
+        B.cdsgd_update(dW, dL, dg, None, lr_l, lr_g, N)
+        oracle.update(W_o, L_o, g, None, lr_l, lr_g, N)
+    else:
+        B.cdsgd_update(dW, None, None, da, lr_l, lr_g, N)
+        oracle.update(W_o, None, None, agg, lr_l, lr_g, N)
+    torch.cuda.synchronize()
+    assert_close(dW.cpu().numpy(), W_o, "w_global")
+    assert_close(dL.cpu().numpy(), L_o, "w_local")
+    assert_bits_equal(dW.cpu().numpy(), W_o, "w_global bits")
+    assert_bits_equal(dL.cpu().numpy(), L_o, "w_local bits")
+    assert guards_intact(wfull, n, 5.0) and guards_intact(lfull, n, 6.0)
+
+
+def _run_layer_list(B, oracle, sizes, N, self_rank, k, t, steps, seed, lr_l=0.4, lr_g=0.1):
+    """Fused step vs oracle vs the three-call composition on an arbitrary layer list."""
+    rng = np.random.default_rng(seed)
+    T = len(sizes)
+    dev = dict(device="cuda")
+    W0 = [rng.normal(0, 0.3, n).astype(np.float32) for n in sizes]
+    # two device copies of the state: one stepped by the fused call, one by the three calls
+    state = []
+    for tag in ("fused", "composed"):
+        st = dict(
+            w_global=[torch.from_numpy(w).cuda() for w in W0],
+            w_local=[torch.zeros(n, dtype=torch.float32, **dev) for n in sizes],
+            residual=[torch.zeros(n, dtype=torch.float32, **dev) for n in sizes],
+            grad=[torch.zeros(n, dtype=torch.float32, **dev) for n in sizes],
+            packed_self=[torch.full((B.packed_words(n),), -1, dtype=torch.int32, **dev) for n in sizes],
+            agg_full=[torch.zeros(n, dtype=torch.float32, **dev) for n in sizes],
+        )
+        state.append(st)
+    peers = [None if j == self_rank else [B.new_packed(n) for n in sizes] for j in range(N)]
+    tensors = [{key: state[0][key][i] for key in state[0]} for i in range(T)]
+    plan = B.Plan(tensors, peers if N > 1 else None, N, self_rank)
+    sims = [oracle.Simulation(W0[i], N, k, t, lr_l, lr_g, self_rank) for i in range(T)]
+    agg_dev = [torch.zeros(n, dtype=torch.float32, **dev) for n in sizes]
+    for s in range(steps):
+        comp_expected = (s % k) != 0
+        for i, n in enumerate(sizes):
+            grads = [rng.normal(0, 1.1 * t, n).astype(np.float32) for _ in range(N)]
+            comp, agg, words = sims[i].step(grads)
+            assert comp == comp_expected
+            for st in state:
+                st["grad"][i].copy_(torch.from_numpy(grads[self_rank]))
+                if not comp:
+                    st["agg_full"][i].copy_(torch.from_numpy(agg))
+            if comp:
+                for j in range(N):
+                    if j != self_rank:
+                        peers[j][i].copy_(torch.from_numpy(words[j].view(np.int32)))
+            sims[i]._last = (comp, agg, words)
+        resid_before = [r.clone() for r in state[0]["residual"]]
+        packed_before = [p.clone() for p in state[0]["packed_self"]]
+        plan.step(s, k, t, lr_l, lr_g)
+        # composition on the second copy
+        c = state[1]
+        for i in range(T):
+            if comp_expected:
+                B.cdsgd_quantize_pack(c["grad"][i], c["residual"][i], c["packed_self"][i], t)
+                streams = [c["packed_self"][i] if j == self_rank else peers[j][i] for j in range(N)]
+                B.cdsgd_decode_sum(streams, agg_dev[i], t)
+                B.cdsgd_update(c["w_global"][i], c["w_local"][i], c["grad"][i], agg_dev[i], lr_l, lr_g, N)
+            else:
+                B.cdsgd_update(c["w_global"][i], c["w_local"][i], c["grad"][i], c["agg_full"][i], lr_l, lr_g, N)
+        torch.cuda.synchronize()
+        f = state[0]
+        for i in range(T):
+            comp, agg, words = sims[i]._last
+            tag = "step %d tensor %d (n=%d)" % (s, i, sizes[i])
+            if comp:
+                assert_bits_equal(f["packed_self"][i].cpu().numpy(), words[self_rank].view(np.int32), "packed " + tag)
+                assert_bits_equal(f["residual"][i].cpu().numpy(), sims[i].residual[self_rank], "residual " + tag)
+                assert_close(agg_dev[i].cpu().numpy(), agg, "agg " + tag)
+            else:
+                assert torch.equal(f["residual"][i], resid_before[i]), "residual touched on correction " + tag
+                assert torch.equal(f["packed_self"][i], packed_before[i]), "packed touched on correction " + tag
+            assert_close(f["w_global"][i].cpu().numpy(), sims[i].w_global, "w_global " + tag)
+            assert_close(f["w_local"][i].cpu().numpy(), sims[i].w_local, "w_local " + tag)
+            assert_bits_equal(f["w_global"][i].cpu().numpy(), sims[i].w_global, "w_global bits " + tag)
+            assert_bits_equal(f["w_local"][i].cpu().numpy(), sims[i].w_local, "w_local bits " + tag)
+            # fused == composition of the three calls, bit for bit
+            for key in ("w_global", "w_local", "residual", "packed_self"):
+                assert torch.equal(f[key][i].view(torch.int32), c[key][i].view(torch.int32)), key + " fused vs composed " + tag
+    plan.destroy()
+
+
+RAGGED = [1, 10, 16, 17, 64, 100, 1000, 4095, 4096, 4097, 9000, 36864, 5, 20011]
+
+
+@pytest.mark.parametrize("t", [0.5, 0.05])
+@pytest.mark.parametrize("N,self_rank", [(1, 0), (2, 0), (2, 1), (4, 0), (5, 2), (8, 7), (16, 0), (16, 9), (17, 16)])
+def test_fused_step_layer_list(B, oracle, N, self_rank, t):
+    _run_layer_list(B, oracle, RAGGED, N, self_rank, k=3, t=t, steps=5, seed=4000 + 17 * N + self_rank)
+
+
+def test_fused_step_max_workers(B, oracle):
+    _run_layer_list(B, oracle, [4100, 33], 64, 31, k=4, t=0.05, steps=3, seed=4999)
+    _run_layer_list(B, oracle, [4100, 33], 64, 63, k=4, t=0.25, steps=3, seed=4998)
