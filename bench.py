@@ -23,6 +23,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per k_fused_compressed launch from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this
+# file, scaled by the same counters' readings for a 1 GiB device copy (FETCH_SIZE x 2.0, WRITE_SIZE
+# x 1.0 on this GPU); summaries in profiles/k_fused_compressed_<workload>.md.
+MEASURED_TRAFFIC_BYTES = {"c4_vgg16": 3.8786e9, "c3_resnet50": 0.71694e9}
+
 
 def _compressed_steps(k, count, start=1):
     """`count` step numbers with step % k != 0."""
@@ -121,16 +126,22 @@ def cpu_baseline(wl, target_seconds=12.0):
                 f.result()
         return n, time.perf_counter() - t0
 
-    n0 = min(avail, 1 << 20)
-    n0, dt0 = timed(n0)
-    n1 = int(min(avail, max(n0, n0 * target_seconds / max(dt0, 1e-6))))
-    n1, dt1 = timed(n1)
+    # size the sample for about `target_seconds` of CPU work in total (all cores together)
+    n0, dt0 = timed(min(avail, 1 << 20))
+    rate = n0 / max(dt0, 1e-6)                                  # elements per second, all cores
+    n1 = int(min(avail, max(n0, rate * target_seconds / cores * 0.5)))
+    reps = max(1, int(round(rate * target_seconds / cores / n1)))
+    dt1 = 0.0
+    for _ in range(reps):                                       # each pass starts from a zero residual
+        n1, dt = timed(n1)
+        dt1 += dt
+    dt1 /= reps
     gbs = n1 * cfg.bytes_per_element / dt1 / 1e9
     return {"value": gbs, "unit": "GB/s", "cores": cores, "kind": "oracle",
             "elems_per_s": n1 / dt1,
             "sample": "first %d elements of tensor %d of %s, one compressed step of worker 0 "
-                      "(quantise+pack, decode-sum of %d streams, both updates), %.1f s wall"
-                      % (n1, big, cfg.name, N, dt1)}
+                      "(quantise+pack, decode-sum of %d streams, both updates), mean of %d passes of %.2f s wall"
+                      % (n1, big, cfg.name, N, reps, dt1)}
 
 
 def main():
@@ -141,6 +152,9 @@ def main():
     ap.add_argument("--workload", default="c4_vgg16")
     ap.add_argument("--no-extra", action="store_true", help="skip the ResNet-50 and 4 GiB workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain device copy of known size (1 GiB read + 1 GiB written, 3 times): "
+                         "under rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings give the counters' scale")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; the other workers' packed gradients are generated "
@@ -153,7 +167,16 @@ def main():
     from paper_2106_10796_amd import binding
     binding.lib()   # fail loudly if the HIP library is not built
 
-    head, wl = time_workload(args.workload, args.steps, args.warmup, want_correction=True, want_unfused=True)
+    if args.calib_copy:
+        src = torch.randn(1 << 28, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
+    head, wl = time_workload(args.workload, args.steps, args.warmup, want_correction=True,
+                             want_unfused=not args.no_extra)
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(wl)
@@ -189,7 +212,7 @@ def main():
                      "achieved": bytes_per_launch / (head["ms_per_step"] * 1e-3) / 1e9,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": bytes_per_launch / (head["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                     "traffic": None},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(head["workload"])},
         "cpu_baseline": cpu,
         "extra": extra,
         "paper_context": "end-to-end time 30% below 2-bit compression on a 16-GPU MXNet cluster at 56 Gbps "
