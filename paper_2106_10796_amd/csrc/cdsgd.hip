@@ -48,6 +48,9 @@
 #ifndef CDSGD_NT_CODES
 #define CDSGD_NT_CODES 0
 #endif
+#ifndef CDSGD_XCD_REMAP
+#define CDSGD_XCD_REMAP 0
+#endif
 #ifndef CDSGD_PEER_BATCH
 #define CDSGD_PEER_BATCH 4
 #endif
@@ -291,6 +294,20 @@ struct ChunkRef {
     unsigned chunk;   // chunk number inside that tensor
 };
 
+// Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b % 8).
+// With the remap, XCD x walks the x-th contiguous eighth of the chunk list instead of
+// every eighth chunk.
+__device__ __forceinline__ unsigned chunk_slot()
+{
+#if CDSGD_XCD_REMAP
+    const unsigned b = blockIdx.x;
+    const unsigned per = gridDim.x >> 3;
+    return b < (per << 3) ? (b & 7u) * per + (b >> 3) : b;
+#else
+    return blockIdx.x;
+#endif
+}
+
 // ---------------------------------------------------------------------------
 // kernels
 // ---------------------------------------------------------------------------
@@ -505,7 +522,7 @@ __global__ __launch_bounds__(CDSGD_BLOCK) void k_fused_compressed(const TensorDe
                                                                   int num_peers, int self, float t,
                                                                   float lr_local, float scale, float bias_t)
 {
-    const ChunkRef cr = chunks[blockIdx.x];
+    const ChunkRef cr = chunks[chunk_slot()];
     const TensorDesc d = tensors[cr.tensor];
     const size_t quad0 = (size_t)cr.chunk * kChunkQuads;
     const uint8_t *const *tp = peers + (size_t)cr.tensor * (size_t)num_peers;
@@ -521,7 +538,7 @@ __global__ __launch_bounds__(CDSGD_BLOCK) void k_fused_correction(const TensorDe
                                                                   const ChunkRef *__restrict__ chunks,
                                                                   float lr_local, float scale)
 {
-    const ChunkRef cr = chunks[blockIdx.x];
+    const ChunkRef cr = chunks[chunk_slot()];
     const TensorDesc d = tensors[cr.tensor];
     const size_t quad0 = (size_t)cr.chunk * kChunkQuads;
     float *wg = d.w_global + 4 * quad0;

@@ -220,3 +220,81 @@ def test_fused_step_layer_list(B, oracle, N, self_rank, t):
 def test_fused_step_max_workers(B, oracle):
     _run_layer_list(B, oracle, [4100, 33], 64, 31, k=4, t=0.05, steps=3, seed=4999)
     _run_layer_list(B, oracle, [4100, 33], 64, 63, k=4, t=0.25, steps=3, seed=4998)
+
+
+def test_tensor_beyond_2_to_32_elements(B, oracle):
+    """One tensor of 2^32 + 4099 elements (17 GB per fp32 buffer): element and byte offsets
+    beyond 32 bits, over a million chunks, ragged end.  All three single-tensor calls and the
+    fused step, compared with the oracle on blocks at the start, around element 2^31, around
+    element 2^32 and at the ragged end (the path is elementwise)."""
+    n = (1 << 32) + 4099
+    N, self_rank, t, lr_l, lr_g, k = 3, 1, 0.05, 0.4, 0.1, 4
+    free, _ = torch.cuda.mem_get_info()
+    if free < 130 * (1 << 30):
+        pytest.skip("needs about 130 GiB of free HBM")
+    nw = B.packed_words(n)
+    blocks = [(0, 8192), ((1 << 31) - 4096, 8192), ((1 << 32) - 8192, 8192 + 4099)]
+
+    def take(x, words=False):
+        return [x[(a // 16 if words else a): (a // 16 + (ln + 15) // 16) if words else a + ln].cpu().numpy()
+                for a, ln in blocks]
+
+    def gauss(seed, std):
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(seed)
+        return torch.empty(n, dtype=torch.float32, device="cuda").normal_(0.0, std, generator=gen)
+
+    # peers' packed streams (their residuals start at zero) via the library itself
+    peers, peer_g = [], []
+    for j in range(N):
+        if j == self_rank:
+            peers.append(None)
+            peer_g.append(None)
+            continue
+        g = gauss(900 + j, 0.06)
+        r = torch.zeros(n, dtype=torch.float32, device="cuda")
+        p = torch.full((nw,), -1, dtype=torch.int32, device="cuda")
+        B.cdsgd_quantize_pack(g, r, p, t)
+        torch.cuda.synchronize()
+        peer_g.append(take(g))
+        # standalone quantize_pack against the oracle on the blocks
+        for b, (a, ln) in enumerate(blocks):
+            r_o = np.zeros(ln, np.float32)
+            words = oracle.quantize_pack(peer_g[j][b], r_o, t)
+            assert_bits_equal(take(p, True)[b], words.view(np.int32), "peer %d packed block %d" % (j, b))
+            assert_bits_equal(take(r)[b], r_o, "peer %d residual block %d" % (j, b))
+        peers.append(p)
+        del g, r
+    g = gauss(901 + self_rank * 7, 0.06)
+    W = gauss(777, 0.3)
+    Wloc = torch.zeros(n, dtype=torch.float32, device="cuda")
+    r = torch.zeros(n, dtype=torch.float32, device="cuda")
+    pself = torch.full((nw,), -1, dtype=torch.int32, device="cuda")
+    g_b, W_b = take(g), take(W)
+    plan = B.Plan([dict(w_global=W, w_local=Wloc, residual=r, grad=g, packed_self=pself)],
+                  [[p] if p is not None else None for p in peers], N, self_rank)
+    plan.step(1, k, t, lr_l, lr_g)       # a compressed step
+    torch.cuda.synchronize()
+    # decode_sum and update standalone on the same inputs (W is already updated, so use copies of blocks only)
+    agg = torch.empty(n, dtype=torch.float32, device="cuda")
+    B.cdsgd_decode_sum([pself if j == self_rank else peers[j] for j in range(N)], agg, t)
+    torch.cuda.synchronize()
+    got = dict(p=take(pself, True), r=take(r), W=take(W), L=take(Wloc), agg=take(agg))
+    for b, (a, ln) in enumerate(blocks):
+        sim = oracle.Simulation(W_b[b], N, k, t, lr_l, lr_g, self_rank)
+        sim.count = 1
+        grads = [g_b[b] if j == self_rank else peer_g[j][b] for j in range(N)]
+        comp, agg_o, words = sim.step(grads)
+        assert comp
+        tag = "block %d (start %d)" % (b, a)
+        assert_bits_equal(got["p"][b], words[self_rank].view(np.int32), "packed_self " + tag)
+        assert_bits_equal(got["r"][b], sim.residual[self_rank], "residual " + tag)
+        assert_close(got["agg"][b], agg_o, "agg " + tag)
+        assert_bits_equal(got["agg"][b], agg_o, "agg bits " + tag)
+        assert_close(got["W"][b], sim.w_global, "w_global " + tag)
+        assert_close(got["L"][b], sim.w_local, "w_local " + tag)
+        assert_bits_equal(got["W"][b], sim.w_global, "w_global bits " + tag)
+        assert_bits_equal(got["L"][b], sim.w_local, "w_local bits " + tag)
+    # the last packed word's unused bits are zero
+    assert int(pself[-1].item()) >> (2 * (n % 16)) == 0
+    plan.destroy()
