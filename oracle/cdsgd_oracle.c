@@ -27,6 +27,8 @@
  *   oracle_full_sum      the sum in eq. 1 / Alg. 1 correction branch
  *   oracle_update        eq. 10 (global) and eq. 11 (local)
  *   oracle_step          Alg. 1, FormalTraining, one pass of the while loop
+ *   oracle_warmup_step   Alg. 1, WARMUP, one pass of the while loop
+ *   oracle_trainer_step  Alg. 1 as a whole: WARMUP for i = 0..n, then FormalTraining
  *
  * Every function here is pinned by tests/test_oracle_pins.py (hand-unrolled
  * recurrence, closed forms, invariants, brute force on tiny inputs).  The four
@@ -160,4 +162,47 @@ int oracle_step(float *w_global, float *w_local, float *const *residual, const f
     }
     oracle_update(w_global, w_local, grad[self], agg, n, lr_local, lr_global, num_workers);
     return compressed;
+}
+
+/* One pass of Alg. 1's WARMUP loop (Sec. 3.2.1) with FP/BP replaced by given
+ * gradients; i is the loop counter before the pass, n the number of warm-up
+ * steps (the loop runs for i = 0..n).  Every pass is plain S-SGD on the global
+ * weights (eq. 1): the server sums the workers' 32-bit gradients and updates.
+ *   i == n     : the local weights are first updated with the own gradient,
+ *                starting from the global weights of this pass (they were copied
+ *                in at i == n-1, or are the initial ones when n == 0)
+ *   i == n - 1 : after the pull, the new global weights are copied into the
+ *                local buffer
+ * No quantisation happens, residuals are not touched. */
+void oracle_warmup_step(float *w_global, float *w_local, const float *const *grad, float *agg, size_t n_elems,
+                        int num_workers, int self, long i, long n, float lr_local, float lr_global)
+{
+    oracle_full_sum(grad, num_workers, agg, n_elems);
+    if (i == n) {
+        /* the local buffer holds W_n here (the copy made at i == n-1; the caller's
+         * initial contents when n == 0) and is updated in place */
+        for (size_t e = 0; e < n_elems; ++e) w_local[e] = fmaf(-lr_local, grad[self][e], w_local[e]);
+    }
+    oracle_update(w_global, NULL, NULL, agg, n_elems, lr_local, lr_global, num_workers);
+    if (i == n - 1) memcpy(w_local, w_global, n_elems * sizeof(float));
+}
+
+/* Alg. 1 end to end for iteration number `iter` (0, 1, 2, ...): iterations
+ * 0..n are WARMUP passes, iteration n+1+c is FormalTraining's pass with
+ * count = c.  Returns 0 for a warm-up pass, 1 for a compressed pass, 2 for a
+ * correction pass. */
+int oracle_trainer_step(float *w_global, float *w_local, float *const *residual, const float *const *grad,
+                        uint32_t *const *word, float *agg, uint8_t *code_scratch, size_t n_elems,
+                        int num_workers, int self, long iter, long warmup_n, int k, float t, float lr_local,
+                        float lr_global)
+{
+    if (iter <= warmup_n) {
+        oracle_warmup_step(w_global, w_local, grad, agg, n_elems, num_workers, self, iter, warmup_n, lr_local,
+                           lr_global);
+        return 0;
+    }
+    return oracle_step(w_global, w_local, residual, grad, word, agg, code_scratch, n_elems, num_workers, self,
+                       iter - warmup_n - 1, k, t, lr_local, lr_global)
+               ? 1
+               : 2;
 }

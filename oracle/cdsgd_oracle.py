@@ -48,6 +48,11 @@ def lib():
                                   ctypes.POINTER(_u32p), _f32p, _u8p, ctypes.c_size_t, ctypes.c_int,
                                   ctypes.c_int, ctypes.c_long, ctypes.c_int, ctypes.c_float,
                                   ctypes.c_float, ctypes.c_float]
+        L.oracle_trainer_step.restype = ctypes.c_int
+        L.oracle_trainer_step.argtypes = [_f32p, _f32p, ctypes.POINTER(_f32p), ctypes.POINTER(_f32p),
+                                          ctypes.POINTER(_u32p), _f32p, _u8p, ctypes.c_size_t, ctypes.c_int,
+                                          ctypes.c_int, ctypes.c_long, ctypes.c_long, ctypes.c_int,
+                                          ctypes.c_float, ctypes.c_float, ctypes.c_float]
         _lib = L
     return _lib
 
@@ -172,3 +177,28 @@ class Simulation:
         self.count += 1
         words = [w.copy() for w in self.word] if c else None
         return bool(c), self.agg.copy(), words
+
+
+class TrainerSimulation(Simulation):
+    """Alg. 1 end to end on one tensor: WARMUP passes for iterations 0..warmup_n, then
+    FormalTraining.  step(grads) returns (mode, agg, words) with mode 0 = warm-up,
+    1 = compressed, 2 = correction."""
+
+    def __init__(self, w0, num_workers, warmup_n, k, t, lr_local, lr_global, self_rank=0):
+        super().__init__(w0, num_workers, k, t, lr_local, lr_global, self_rank)
+        self.warmup_n = int(warmup_n)
+        self.iteration = 0
+
+    def step(self, grads):
+        assert len(grads) == self.N
+        for g in grads:
+            _chk(g, np.float32, self.n)
+        mode = lib().oracle_trainer_step(_p(self.w_global, _f32p), _p(self.w_local, _f32p),
+                                         _ptr_array(self.residual, _f32p), _ptr_array(grads, _f32p),
+                                         _ptr_array(self.word, _u32p), _p(self.agg, _f32p),
+                                         _p(self._code, _u8p), self.n, self.N, self.self_rank,
+                                         self.iteration, self.warmup_n, self.k, self.t, self.lr_local,
+                                         self.lr_global)
+        self.iteration += 1
+        words = [w.copy() for w in self.word] if mode == 1 else None
+        return int(mode), self.agg.copy(), words

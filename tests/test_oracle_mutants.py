@@ -40,6 +40,15 @@ MUTANTS = [
      "oracle_full_sum(grad, num_workers, agg, n); for (int j = 0; j < num_workers; ++j) memset(residual[j], 0, n * sizeof(float));"),
     ("shared_residual", "oracle_quantize(grad[j], residual[j], code_scratch, n, t);",
      "oracle_quantize(grad[j], residual[0], code_scratch, n, t);"),
+    ("warmup_copy_one_pass_late", "if (i == n - 1) memcpy(w_local, w_global, n_elems * sizeof(float));",
+     "if (i == n) memcpy(w_local, w_global, n_elems * sizeof(float));"),
+    ("warmup_copy_before_update", "    oracle_update(w_global, NULL, NULL, agg, n_elems, lr_local, lr_global, num_workers);\n    if (i == n - 1) memcpy",
+     "    if (i == n - 1) memcpy(w_local, w_global, n_elems * sizeof(float));\n    oracle_update(w_global, NULL, NULL, agg, n_elems, lr_local, lr_global, num_workers);\n    if (0) memcpy"),
+    ("warmup_local_update_every_pass", "if (i == n) {\n        /* the local buffer", "if (i <= n) {\n        /* the local buffer"),
+    ("warmup_local_uses_global_rate", "w_local[e] = fmaf(-lr_local, grad[self][e], w_local[e]);",
+     "w_local[e] = fmaf(-lr_global, grad[self][e], w_local[e]);"),
+    ("warmup_one_pass_short", "if (iter <= warmup_n) {", "if (iter < warmup_n) {"),
+    ("formal_count_not_reset", "iter - warmup_n - 1, k, t,", "iter, k, t,"),
     ("local_uses_wrong_worker", "oracle_update(w_global, w_local, grad[self],", "oracle_update(w_global, w_local, grad[num_workers - 1 - self],"),
 ]
 

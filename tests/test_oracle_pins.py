@@ -480,3 +480,60 @@ def test_first_step_fire_rate_matches_laplace_tail(oracle):
     p = (code != 0).mean()
     assert abs(p - np.exp(-2.5)) < 4 * np.sqrt(np.exp(-2.5) / n)
     assert abs((code == 1).mean() - (code == 2).mean()) < 0.003
+
+
+# --------------------------------------------------------------------------
+# Alg. 1 end to end: WARMUP, then FormalTraining
+# --------------------------------------------------------------------------
+def test_hand_unrolled_warmup_then_formal(oracle):
+    rows = _read_golden("hand_unrolled_warmup_n1.txt")
+    _, n, N, wn, k, t, lrl, lrg, w0 = rows[0].split()
+    sim = oracle.TrainerSimulation(f32([float(w0)] * int(n)), int(N), int(wn), int(k), float(t), float(lrl),
+                                   float(lrg))
+    for row in rows[1:]:
+        lhs, rhs = row.split("|")
+        g = [float(x) for x in lhs.split()[1:]]
+        mode, agg, W, Wloc, r0, r1 = rhs.split()
+        got_mode, got_agg, _ = sim.step([f32([g[0]]), f32([g[1]])])
+        assert got_mode == int(mode)
+        assert got_agg[0] == F32(float(agg))
+        assert sim.w_global[0] == F32(float(W))
+        assert sim.w_local[0] == F32(float(Wloc))
+        assert sim.residual[0][0] == F32(float(r0)) and sim.residual[1][0] == F32(float(r1))
+
+
+@pytest.mark.parametrize("warmup_n", [0, 1, 2, 5])
+def test_warmup_is_ssgd_and_hands_over_to_formal_training(oracle, warmup_n):
+    """WARMUP runs for i = 0..n as plain S-SGD (eq. 1, exact on dyadic inputs); the local
+    buffer receives W_n after pass n-1 and W_n - lr_local * g_n in pass n; pass n+1 is
+    FormalTraining's first pass (count 0, a correction pass), pass n+2 is compressed."""
+    rng = np.random.default_rng(30 + warmup_n)
+    n, N, k, t, lr_l, lr_g = 41, 4, 3, 0.5, 0.25, 0.125
+    w0 = (rng.integers(-2048, 2048, n) / 64.0).astype(np.float32)
+    sim = oracle.TrainerSimulation(w0, N, warmup_n, k, t, lr_l, lr_g, self_rank=2)
+    ref = w0.astype(np.float64)
+    modes = []
+    for it in range(warmup_n + 1 + 2 * k):
+        grads = [(rng.integers(-64, 65, n) / 64.0).astype(np.float32) for _ in range(N)]
+        w_before = sim.w_global.copy()
+        loc_before = sim.w_local.copy()
+        mode, agg, words = sim.step(grads)
+        modes.append(mode)
+        if it <= warmup_n:
+            ref = ref - (lr_g / N) * np.sum([g.astype(np.float64) for g in grads], axis=0)
+            assert np.array_equal(sim.w_global.astype(np.float64), ref)          # eq. 1, exactly
+            for j in range(N):
+                assert not sim.residual[j].any()
+            if it == warmup_n - 1:
+                assert np.array_equal(sim.w_local, sim.w_global)                 # copy after the pull
+            elif it == warmup_n:
+                assert np.array_equal(sim.w_local.astype(np.float64),
+                                      w_before.astype(np.float64) - lr_l * grads[2].astype(np.float64))
+            else:
+                assert np.array_equal(sim.w_local, loc_before)                   # untouched before n-1
+        else:
+            # formal training: local weights from the pre-pass global weights, own 32-bit gradient
+            assert np.array_equal(sim.w_local.astype(np.float64),
+                                  w_before.astype(np.float64) - lr_l * grads[2].astype(np.float64))
+    expect = [0] * (warmup_n + 1) + [2 if c % k == 0 else 1 for c in range(2 * k)]
+    assert modes == expect
