@@ -83,6 +83,31 @@ def time_workload(name, steps, warmup, want_correction=True, want_unfused=False)
     return out, wl
 
 
+def time_correction_sum(name, steps, warmup):
+    """Correction pass that sums the N workers' fp32 gradients in the kernel (Alg. 1, else-branch):
+    reads W and N gradients, writes W and W_loc = 12 + 4N bytes per element."""
+    import torch
+    from paper_2106_10796_amd import runner, synth
+    cfg = synth.config(name)
+    wl = runner.Workload(cfg, peer_residuals=False, full_grads=True)
+    wl.prepare_step(0)
+    stream = torch.cuda.current_stream()
+    for _ in range(max(warmup, 1)):
+        wl.fused_step(0)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(steps):
+        wl.fused_step(0)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    bpe = 12.0 + 4.0 * cfg.num_workers
+    wl.destroy()
+    return {"ms_per_step": ms, "bytes_per_element": bpe, "gbs": cfg.elements * bpe / (ms * 1e-3) / 1e9,
+            "frac_hbm_peak": cfg.elements * bpe / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+
 def cpu_baseline(wl, target_seconds=12.0):
     """The oracle as it stands, timed on this host: worker 0's fused-equivalent work
     (quantise + pack own gradient, decode-and-sum N streams, both updates) on a bounded
@@ -185,6 +210,9 @@ def main():
     torch.cuda.empty_cache()
     extra = {"headline": head}
     if not args.no_extra:
+        extra["correction_with_kernel_sum_" + args.workload] = time_correction_sum(
+            args.workload, max(3, args.steps // 4), max(1, args.warmup // 2))
+        torch.cuda.empty_cache()
         for name in ("c3_resnet50", "c5_flat4g"):
             if name == args.workload:
                 continue

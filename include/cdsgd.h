@@ -47,7 +47,7 @@ typedef enum {
     CDSGD_OK = 0,
     CDSGD_ERR_NULL = 1,    /* a required pointer is NULL */
     CDSGD_ERR_SIZE = 2,    /* n == 0, num_tensors < 1, or a size too large for the launch */
-    CDSGD_ERR_PARAM = 3,   /* threshold not finite or <= 0, k < 1, step < 0, rate not finite */
+    CDSGD_ERR_PARAM = 3,   /* threshold not finite or <= 0, k < 1, step < 0, rate not finite, bad warm-up index */
     CDSGD_ERR_ALIGN = 4,   /* pointer alignment (see above) */
     CDSGD_ERR_WORKERS = 5, /* num_workers < 1 or > CDSGD_MAX_WORKERS, self out of range */
     CDSGD_ERR_DEVICE = 6   /* a HIP call failed (allocation, copy, launch) */
@@ -118,8 +118,8 @@ typedef struct cdsgd_plan cdsgd_plan;
 
 /*
  * Build a plan: copies the layer list, the peers' pointers and a chunk table to
- * the device (one small allocation, one synchronous copy; the only call that
- * allocates).  The plan borrows every data pointer: the buffers must stay alive
+ * the device (one small allocation, one synchronous copy; only this call and
+ * cdsgd_plan_bind_full_grads allocate).  The plan borrows every data pointer: the buffers must stay alive
  * and in place while the plan is used.
  *   tensors      host array [num_tensors]
  *   peers        host array [num_workers] of host arrays [num_tensors] of device
@@ -135,7 +135,7 @@ int cdsgd_plan_create(const cdsgd_tensor *tensors, int num_tensors,
                       const uint32_t *const *const *peers, int num_workers, int self,
                       cdsgd_plan **out);
 
-/* Frees the plan's device table.  NULL is accepted. */
+/* Frees the plan's device tables.  NULL is accepted. */
 int cdsgd_plan_destroy(cdsgd_plan *plan);
 
 /*
@@ -145,11 +145,58 @@ int cdsgd_plan_destroy(cdsgd_plan *plan);
  *                  packed_self written), decode and sum the N streams with the
  *                  own codes at position `self`, then both update rules.
  *   step % k == 0  correction: no quantisation, residual and packed_self are not
- *                  touched; both update rules with agg_full as the aggregate
- *                  (CDSGD_ERR_NULL if a tensor has none).
+ *                  touched; both update rules with the fp32 sum of all gradients as
+ *                  the aggregate: summed in the kernel if full gradients are bound
+ *                  (cdsgd_plan_bind_full_grads), else read from agg_full
+ *                  (CDSGD_ERR_NULL if the plan has neither).
  */
 int cdsgd_step_fused(cdsgd_plan *plan, long step, int k, float threshold, float lr_local,
                      float lr_global, void *hip_stream);
+
+/*
+ * Let correction and warm-up passes sum the workers' 32-bit gradients themselves
+ * (Alg. 1, else-branch and WARMUP; the sum of eq. 1) instead of reading agg_full:
+ * one launch then reads W and the N gradients and writes W and W_loc.
+ *   peer_grads  host array [num_workers] of host arrays [num_tensors] of device
+ *               pointers to fp32[n] (what the server would receive); row `self` is
+ *               ignored (the own gradient is cdsgd_tensor.grad) and may be NULL.
+ * Copies the pointers to the device (allocates on first use, synchronous copy);
+ * the plan borrows the buffers.  May be called again to rebind.  With
+ * num_workers == 1 nothing is needed and the call is a no-op.
+ */
+int cdsgd_plan_bind_full_grads(cdsgd_plan *plan, const float *const *const *peer_grads);
+
+/*
+ * One pass of Alg. 1's WARMUP loop (i = 0 .. warmup_steps) for every tensor of the
+ * plan: plain S-SGD on the global weights (eq. 1) with the fp32 sum of all
+ * gradients (summed in the kernel if full gradients are bound, else agg_full;
+ * CDSGD_ERR_NULL if the plan has neither).
+ *   i <  warmup_steps - 1   w_local is not written
+ *   i == warmup_steps - 1   w_local = the new global weights (the copy after the pull)
+ *   i == warmup_steps       w_local = W - lr_local * grad from the pre-pass W (the
+ *                           local buffer holds exactly that W at this point)
+ * i outside [0, warmup_steps] is CDSGD_ERR_PARAM.
+ */
+int cdsgd_step_warmup(cdsgd_plan *plan, long i, long warmup_steps, float lr_local, float lr_global,
+                      void *hip_stream);
+
+/*
+ * Alg. 1 as a whole, as a counter around cdsgd_step_warmup and cdsgd_step_fused:
+ * iterations 0 .. warmup_steps are WARMUP passes, iteration warmup_steps + 1 + c is
+ * FormalTraining's pass with count = c.  The trainer borrows the plan (destroy the
+ * trainer first) and owns nothing on the device.
+ */
+typedef enum { CDSGD_PASS_WARMUP = 0, CDSGD_PASS_COMPRESSED = 1, CDSGD_PASS_CORRECTION = 2 } cdsgd_pass;
+typedef struct cdsgd_trainer cdsgd_trainer;
+
+int cdsgd_trainer_create(cdsgd_plan *plan, long warmup_steps, int k, float threshold, float lr_local,
+                         float lr_global, cdsgd_trainer **out);
+/* Enqueue the next iteration; *pass_kind (may be NULL) receives a cdsgd_pass.  On an
+ * error nothing is enqueued and the iteration number does not advance. */
+int cdsgd_trainer_step(cdsgd_trainer *trainer, void *hip_stream, int *pass_kind);
+/* Number of iterations enqueued so far (-1 for NULL). */
+long cdsgd_trainer_iteration(const cdsgd_trainer *trainer);
+int cdsgd_trainer_destroy(cdsgd_trainer *trainer);
 
 #ifdef __cplusplus
 }

@@ -13,6 +13,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libcdsgd.so")
 
 MAX_WORKERS = 64
+PASS_WARMUP, PASS_COMPRESSED, PASS_CORRECTION = 0, 1, 2
 OK, ERR_NULL, ERR_SIZE, ERR_PARAM, ERR_ALIGN, ERR_WORKERS, ERR_DEVICE = range(7)
 
 
@@ -59,6 +60,18 @@ def lib():
         L.cdsgd_plan_destroy.argtypes = [vp]
         L.cdsgd_step_fused.restype = i
         L.cdsgd_step_fused.argtypes = [vp, ctypes.c_long, i, f, f, f, vp]
+        L.cdsgd_plan_bind_full_grads.restype = i
+        L.cdsgd_plan_bind_full_grads.argtypes = [vp, ctypes.POINTER(ctypes.POINTER(vp))]
+        L.cdsgd_step_warmup.restype = i
+        L.cdsgd_step_warmup.argtypes = [vp, ctypes.c_long, ctypes.c_long, f, f, vp]
+        L.cdsgd_trainer_create.restype = i
+        L.cdsgd_trainer_create.argtypes = [vp, ctypes.c_long, i, f, f, f, ctypes.POINTER(vp)]
+        L.cdsgd_trainer_step.restype = i
+        L.cdsgd_trainer_step.argtypes = [vp, vp, ctypes.POINTER(i)]
+        L.cdsgd_trainer_iteration.restype = ctypes.c_long
+        L.cdsgd_trainer_iteration.argtypes = [vp]
+        L.cdsgd_trainer_destroy.restype = i
+        L.cdsgd_trainer_destroy.argtypes = [vp]
         _lib = L
     return _lib
 
@@ -159,6 +172,7 @@ class Plan:
                     row[i] = _dev(peers[j][i], PACKED_DTYPE, packed_words(n), "peers[%d][%d]" % (j, i)).value
                 self._rows.append(row)
                 rows[j] = ctypes.cast(row, ctypes.POINTER(ctypes.c_void_p))
+        self._sizes = [t["w_global"].numel() for t in tensors]
         handle = ctypes.c_void_p()
         st = lib().cdsgd_plan_create(arr, T, rows if peers is not None else None, int(num_workers),
                                      int(self_rank), ctypes.byref(handle))
@@ -171,11 +185,70 @@ class Plan:
                                     float(lr_global), _stream())
         _check(st, "cdsgd_step_fused")
 
+    def bind_full_grads(self, peer_grads):
+        """peer_grads[j][i]: worker j's fp32 gradient of tensor i; entry self_rank may be None
+        (cdsgd_plan_bind_full_grads).  Correction and warm-up passes then sum in the kernel."""
+        T = len(self._sizes)
+        rows = (ctypes.POINTER(ctypes.c_void_p) * max(self.num_workers, 1))()
+        keep = []
+        for j in range(self.num_workers):
+            if peer_grads[j] is None:
+                rows[j] = ctypes.POINTER(ctypes.c_void_p)()
+                continue
+            row = (ctypes.c_void_p * max(T, 1))()
+            for i in range(T):
+                row[i] = _dev(peer_grads[j][i], torch.float32, self._sizes[i], "peer_grads[%d][%d]" % (j, i)).value
+            keep.append(row)
+            rows[j] = ctypes.cast(row, ctypes.POINTER(ctypes.c_void_p))
+        st = lib().cdsgd_plan_bind_full_grads(self._handle, rows)
+        _check(st, "cdsgd_plan_bind_full_grads")
+        self._keep_full = peer_grads
+
+    def step_warmup(self, i, warmup_steps, lr_local, lr_global):
+        st = lib().cdsgd_step_warmup(self._handle, int(i), int(warmup_steps), float(lr_local), float(lr_global),
+                                     _stream())
+        _check(st, "cdsgd_step_warmup")
+
     def destroy(self):
         if self._handle is not None and self._handle.value:
             lib().cdsgd_plan_destroy(self._handle)
         self._handle = None
         self._keep = None
+        self._keep_full = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+class Trainer:
+    """Alg. 1 end to end as a counter around a plan (cdsgd_trainer_*)."""
+
+    def __init__(self, plan: Plan, warmup_steps, k, threshold, lr_local, lr_global):
+        self._plan = plan
+        handle = ctypes.c_void_p()
+        st = lib().cdsgd_trainer_create(plan._handle, int(warmup_steps), int(k), float(threshold),
+                                        float(lr_local), float(lr_global), ctypes.byref(handle))
+        _check(st, "cdsgd_trainer_create")
+        self._handle = handle
+
+    def step(self) -> int:
+        """Enqueue the next iteration; returns PASS_WARMUP / PASS_COMPRESSED / PASS_CORRECTION."""
+        kind = ctypes.c_int(-1)
+        st = lib().cdsgd_trainer_step(self._handle, _stream(), ctypes.byref(kind))
+        _check(st, "cdsgd_trainer_step")
+        return kind.value
+
+    @property
+    def iteration(self) -> int:
+        return int(lib().cdsgd_trainer_iteration(self._handle))
+
+    def destroy(self):
+        if self._handle is not None and self._handle.value:
+            lib().cdsgd_trainer_destroy(self._handle)
+        self._handle = None
 
     def __del__(self):
         try:

@@ -533,20 +533,93 @@ __global__ __launch_bounds__(CDSGD_BLOCK) void k_fused_compressed(const TensorDe
                                 scale, bias_t);
 }
 
-// Correction step over the layer list: no quantisation, agg_full is the aggregate.
-__global__ __launch_bounds__(CDSGD_BLOCK) void k_fused_correction(const TensorDesc *__restrict__ tensors,
-                                                                  const ChunkRef *__restrict__ chunks,
-                                                                  float lr_local, float scale)
+// Passes that use the workers' 32-bit gradients (Alg. 1: WARMUP passes and the
+// correction branch of FormalTraining; eq. 1).  No quantisation, residual and
+// packed streams are not touched.
+//   SUM    true:  the aggregate is summed here from the N gradients, worker order,
+//                 own gradient at position `self` (reads 4N + 4, writes 4 or 8 B/element)
+//          false: the aggregate is read from agg_full
+//   LOCAL  kLocalNone: global rule only              (WARMUP, i < n-1)
+//          kLocalCopy: w_local = new global weight   (WARMUP, i == n-1, the copy after the pull)
+//          kLocalRule: w_local = W - lr_local * g    (WARMUP, i == n; correction passes; eq. 11)
+constexpr int kLocalNone = 0, kLocalCopy = 1, kLocalRule = 2;
+
+template <bool G, bool SUM, int LOCAL>
+__device__ __forceinline__ void full_chunk(const TensorDesc &d, const float *const *__restrict__ pg,
+                                           int num_peers, int self, size_t quad0, unsigned rem_elems,
+                                           float lr_local, float scale)
+{
+    const unsigned tid = threadIdx.x;
+    float *__restrict__ wg = d.w_global + 4 * quad0;
+    float *__restrict__ wl = d.w_local + 4 * quad0;
+    const float *__restrict__ grad = d.grad + 4 * quad0;
+    f4 w[kQpl], g[kQpl], a[kQpl];
+    int cnt[kQpl];
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) {
+        const unsigned qi = j * kBlock + tid;
+        cnt[j] = quad_count<G>(rem_elems, qi);
+        w[j] = ld4g<G>(wg, qi, cnt[j]);
+        if (SUM || LOCAL == kLocalRule) g[j] = ld4g<G>(grad, qi, cnt[j]);
+        if (SUM) a[j] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+        else a[j] = ld4g<G>(d.agg_full + 4 * quad0, qi, cnt[j]);
+    }
+    if (SUM) {
+        auto add_range = [&](int p_begin, int p_end) {
+            int p = p_begin;
+            for (; p + 4 <= p_end; p += 4) {
+                f4 v[4][kQpl];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (unsigned j = 0; j < kQpl; ++j)
+                        v[i][j] = ld4g<G>(pg[p + i] + 4 * quad0, j * kBlock + tid, cnt[j]);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (unsigned j = 0; j < kQpl; ++j) a[j] = a[j] + v[i][j];
+            }
+            for (; p < p_end; ++p) {
+#pragma unroll
+                for (unsigned j = 0; j < kQpl; ++j)
+                    a[j] = a[j] + ld4g<G>(pg[p] + 4 * quad0, j * kBlock + tid, cnt[j]);
+            }
+        };
+        add_range(0, self);
+#pragma unroll
+        for (unsigned j = 0; j < kQpl; ++j) a[j] = a[j] + g[j];
+        add_range(self, num_peers);
+    }
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) {
+        const unsigned qi = j * kBlock + tid;
+        f4 vg, vl;
+#pragma unroll
+        for (unsigned c = 0; c < 4; ++c) {
+            vg[c] = __builtin_fmaf(-scale, a[j][c], w[j][c]);
+            vl[c] = LOCAL == kLocalRule ? __builtin_fmaf(-lr_local, g[j][c], w[j][c]) : vg[c];
+        }
+        if (LOCAL != kLocalNone) st4g<G>(wl, qi, cnt[j], vl);
+        st4g<G>(wg, qi, cnt[j], vg);
+    }
+}
+
+// peer_grads: [num_tensors][num_peers] pointers (own row left out), or unused when !SUM.
+template <bool SUM, int LOCAL>
+__global__ __launch_bounds__(CDSGD_BLOCK) void k_fused_full(const TensorDesc *__restrict__ tensors,
+                                                            const ChunkRef *__restrict__ chunks,
+                                                            const float *const *__restrict__ peer_grads,
+                                                            int num_peers, int self, float lr_local,
+                                                            float scale)
 {
     const ChunkRef cr = chunks[chunk_slot()];
     const TensorDesc d = tensors[cr.tensor];
     const size_t quad0 = (size_t)cr.chunk * kChunkQuads;
-    float *wg = d.w_global + 4 * quad0;
-    float *wl = d.w_local + 4 * quad0;
-    const float *grad = d.grad + 4 * quad0;
-    const float *agg = d.agg_full + 4 * quad0;
-    if (cr.chunk < d.ext.full_chunks) update_chunk<false, true, true>(wg, wl, grad, agg, kChunkElems, lr_local, scale);
-    else update_chunk<true, true, true>(wg, wl, grad, agg, d.ext.tail_elems, lr_local, scale);
+    const float *const *pg = SUM ? peer_grads + (size_t)cr.tensor * (size_t)num_peers : nullptr;
+    if (cr.chunk < d.ext.full_chunks)
+        full_chunk<false, SUM, LOCAL>(d, pg, num_peers, self, quad0, kChunkElems, lr_local, scale);
+    else
+        full_chunk<true, SUM, LOCAL>(d, pg, num_peers, self, quad0, d.ext.tail_elems, lr_local, scale);
 }
 
 // ---------------------------------------------------------------------------
@@ -600,7 +673,45 @@ struct cdsgd_plan {
     int self = 0;
     unsigned num_chunks = 0;
     bool has_agg_full = false;
+    const float **peer_grads = nullptr;  // second allocation, made by cdsgd_plan_bind_full_grads
 };
+
+struct cdsgd_trainer {
+    cdsgd_plan *plan = nullptr;
+    long warmup_steps = 0;
+    int k = 1;
+    float threshold = 0.0f, lr_local = 0.0f, lr_global = 0.0f;
+    long iteration = 0;
+};
+
+namespace {
+
+// Launch one full-gradient pass (see k_fused_full) for a plan.
+int launch_full_pass(cdsgd_plan *plan, int local_mode, float lr_local, float lr_global, void *hip_stream)
+{
+    const bool sum = plan->peer_grads != nullptr || plan->num_workers == 1;
+    if (!sum && !plan->has_agg_full) return CDSGD_ERR_NULL;
+    const float scale = lr_global / (float)plan->num_workers;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const dim3 grid(plan->num_chunks), block(kBlock);
+    const int np = plan->num_workers - 1;
+#define CDSGD_LAUNCH_FULL(SUM, LOCAL)                                                                          \
+    hipLaunchKernelGGL((k_fused_full<SUM, LOCAL>), grid, block, 0, s, plan->tensors, plan->chunks,               \
+                       plan->peer_grads, np, plan->self, lr_local, scale)
+    if (sum) {
+        if (local_mode == kLocalNone) CDSGD_LAUNCH_FULL(true, kLocalNone);
+        else if (local_mode == kLocalCopy) CDSGD_LAUNCH_FULL(true, kLocalCopy);
+        else CDSGD_LAUNCH_FULL(true, kLocalRule);
+    } else {
+        if (local_mode == kLocalNone) CDSGD_LAUNCH_FULL(false, kLocalNone);
+        else if (local_mode == kLocalCopy) CDSGD_LAUNCH_FULL(false, kLocalCopy);
+        else CDSGD_LAUNCH_FULL(false, kLocalRule);
+    }
+#undef CDSGD_LAUNCH_FULL
+    return launch_status();
+}
+
+}  // namespace
 
 extern "C" {
 
@@ -787,6 +898,10 @@ int cdsgd_plan_destroy(cdsgd_plan *plan)
         (void)hipGetLastError();
         rc = CDSGD_ERR_DEVICE;
     }
+    if (plan->peer_grads && hipFree((void *)plan->peer_grads) != hipSuccess) {
+        (void)hipGetLastError();
+        rc = CDSGD_ERR_DEVICE;
+    }
     delete plan;
     return rc;
 }
@@ -798,7 +913,7 @@ int cdsgd_step_fused(cdsgd_plan *plan, long step, int k, float threshold, float 
     if (k < 1 || step < 0 || !good_threshold(threshold) || !std::isfinite(lr_local) || !std::isfinite(lr_global))
         return CDSGD_ERR_PARAM;
     const bool compressed = (step % k) != 0;
-    if (!compressed && !plan->has_agg_full) return CDSGD_ERR_NULL;
+    if (!compressed) return launch_full_pass(plan, kLocalRule, lr_local, lr_global, hip_stream);
     const float scale = lr_global / (float)plan->num_workers;
     hipStream_t s = (hipStream_t)hip_stream;
     const dim3 grid(plan->num_chunks), block(kBlock);
@@ -811,10 +926,101 @@ int cdsgd_step_fused(cdsgd_plan *plan, long step, int k, float threshold, float 
         else
             hipLaunchKernelGGL(k_fused_compressed<false>, grid, block, 0, s, plan->tensors, plan->chunks,
                                plan->peers, num_peers, plan->self, threshold, lr_local, scale, bias_t);
-    } else {
-        hipLaunchKernelGGL(k_fused_correction, grid, block, 0, s, plan->tensors, plan->chunks, lr_local, scale);
     }
     return launch_status();
+}
+
+int cdsgd_plan_bind_full_grads(cdsgd_plan *plan, const float *const *const *peer_grads)
+{
+    if (!plan) return CDSGD_ERR_NULL;
+    const int np = plan->num_workers - 1;
+    if (np == 0) return CDSGD_OK;  // a single worker's sum is its own gradient
+    if (!peer_grads) return CDSGD_ERR_NULL;
+    std::vector<const float *> image((size_t)plan->num_tensors * (size_t)np);
+    for (int j = 0, slot = 0; j < plan->num_workers; ++j) {
+        if (j == plan->self) continue;
+        if (!peer_grads[j]) return CDSGD_ERR_NULL;
+        for (int i = 0; i < plan->num_tensors; ++i) {
+            if (!peer_grads[j][i]) return CDSGD_ERR_NULL;
+            if (!aligned(peer_grads[j][i], 16)) return CDSGD_ERR_ALIGN;
+            image[(size_t)i * (size_t)np + (size_t)slot] = peer_grads[j][i];
+        }
+        ++slot;
+    }
+    const size_t bytes = image.size() * sizeof(const float *);
+    void *dev = (void *)plan->peer_grads;
+    if (!dev && hipMalloc(&dev, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return CDSGD_ERR_DEVICE;
+    }
+    if (hipMemcpy(dev, image.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipGetLastError();
+        if (!plan->peer_grads) (void)hipFree(dev);
+        return CDSGD_ERR_DEVICE;
+    }
+    plan->peer_grads = (const float **)dev;
+    return CDSGD_OK;
+}
+
+int cdsgd_step_warmup(cdsgd_plan *plan, long i, long warmup_steps, float lr_local, float lr_global,
+                      void *hip_stream)
+{
+    if (!plan) return CDSGD_ERR_NULL;
+    if (warmup_steps < 0 || i < 0 || i > warmup_steps || !std::isfinite(lr_local) || !std::isfinite(lr_global))
+        return CDSGD_ERR_PARAM;
+    const int mode = i == warmup_steps ? kLocalRule : (i == warmup_steps - 1 ? kLocalCopy : kLocalNone);
+    return launch_full_pass(plan, mode, lr_local, lr_global, hip_stream);
+}
+
+int cdsgd_trainer_create(cdsgd_plan *plan, long warmup_steps, int k, float threshold, float lr_local,
+                         float lr_global, cdsgd_trainer **out)
+{
+    if (!out) return CDSGD_ERR_NULL;
+    *out = nullptr;
+    if (!plan) return CDSGD_ERR_NULL;
+    if (warmup_steps < 0 || k < 1 || !good_threshold(threshold) || !std::isfinite(lr_local) ||
+        !std::isfinite(lr_global))
+        return CDSGD_ERR_PARAM;
+    cdsgd_trainer *t = new (std::nothrow) cdsgd_trainer;
+    if (!t) return CDSGD_ERR_DEVICE;
+    t->plan = plan;
+    t->warmup_steps = warmup_steps;
+    t->k = k;
+    t->threshold = threshold;
+    t->lr_local = lr_local;
+    t->lr_global = lr_global;
+    t->iteration = 0;
+    *out = t;
+    return CDSGD_OK;
+}
+
+int cdsgd_trainer_step(cdsgd_trainer *trainer, void *hip_stream, int *pass_kind)
+{
+    if (!trainer) return CDSGD_ERR_NULL;
+    const long it = trainer->iteration;
+    int rc, kind;
+    if (it <= trainer->warmup_steps) {
+        kind = CDSGD_PASS_WARMUP;
+        rc = cdsgd_step_warmup(trainer->plan, it, trainer->warmup_steps, trainer->lr_local, trainer->lr_global,
+                               hip_stream);
+    } else {
+        const long count = it - trainer->warmup_steps - 1;
+        kind = (count % trainer->k) != 0 ? CDSGD_PASS_COMPRESSED : CDSGD_PASS_CORRECTION;
+        rc = cdsgd_step_fused(trainer->plan, count, trainer->k, trainer->threshold, trainer->lr_local,
+                              trainer->lr_global, hip_stream);
+    }
+    if (rc != CDSGD_OK) return rc;  // the iteration counter only advances on success
+    trainer->iteration = it + 1;
+    if (pass_kind) *pass_kind = kind;
+    return CDSGD_OK;
+}
+
+long cdsgd_trainer_iteration(const cdsgd_trainer *trainer) { return trainer ? trainer->iteration : -1; }
+
+int cdsgd_trainer_destroy(cdsgd_trainer *trainer)
+{
+    delete trainer;
+    return CDSGD_OK;
 }
 
 }  // extern "C"

@@ -24,7 +24,7 @@ ALIGN_ELEMS = 1024
 
 class Workload:
     def __init__(self, cfg: synth.Config, device="cuda", dense: bool = False, self_rank: int = 0,
-                 peer_residuals: bool = True):
+                 peer_residuals: bool = True, full_grads: bool = False):
         self.cfg = cfg
         self.device = torch.device(device)
         self.dense = dense
@@ -51,11 +51,21 @@ class Workload:
             None if (j == self.self_rank or not peer_residuals) else torch.zeros(self.total, **f32)
             for j in range(self.N)]
         self._scratch = torch.zeros(self.total, **f32)   # a peer's gradient, one worker at a time
+        # full_grads: every peer's 32-bit gradient stays resident (what the server side would hold on a
+        # correction or warm-up pass) and those passes sum in the kernel instead of reading agg_full
+        self.peer_grad: List[Optional[torch.Tensor]] = [
+            None if (j == self.self_rank or not full_grads) else torch.zeros(self.total, **f32)
+            for j in range(self.N)]
+        self.full_grads = full_grads
         self._agg = None                                 # decoded aggregate of the unfused path
         for i in range(cfg.num_tensors):
             synth.fill_weight(self.view(self.w_global, i), cfg, i)
         self.w_local.copy_(self.w_global)
         self.plan = binding.Plan(self._plan_tensors(), self._plan_peers(), self.N, self.self_rank)
+        if full_grads and self.N > 1:
+            self.plan.bind_full_grads([None if j == self.self_rank else
+                                       [self.view(self.peer_grad[j], i) for i in range(cfg.num_tensors)]
+                                       for j in range(self.N)])
 
     # -- views ------------------------------------------------------------
     def view(self, arena: torch.Tensor, i: int) -> torch.Tensor:
@@ -92,13 +102,16 @@ class Workload:
         for i in range(self.cfg.num_tensors):
             self.gen_grad(worker, step, i, out=self.view(arena, i))
 
-    def prepare_step(self, step: int, capture=None):
+    def prepare_step(self, step: int, capture=None, compressed=None):
         """Everything the observed worker's step consumes: its own gradient, and either the
-        peers' packed streams (compressed step) or the fp32 sum of all gradients (correction).
+        peers' packed streams (compressed step) or the fp32 sum of all gradients and, with
+        full_grads, the peers' gradients themselves (correction or warm-up pass).
 
+        `step` seeds the gradients; `compressed` overrides the step % k rule (a trainer with
+        warm-up passes numbers its iterations differently).
         capture: optional list of (tensor, start, length); the matching slices of every
         worker's gradient are returned as host arrays, out[worker][slice] (for checkers)."""
-        comp = self.compressed(step)
+        comp = self.compressed(step) if compressed is None else bool(compressed)
         t = self.cfg.threshold
         if not comp:
             self.agg_full.zero_()
@@ -108,8 +121,8 @@ class Workload:
                 self._fill_arena(self.grad, j, step)
                 g = self.grad
             else:
-                self._fill_arena(self._scratch, j, step)
-                g = self._scratch
+                g = self.peer_grad[j] if self.full_grads else self._scratch
+                self._fill_arena(g, j, step)
                 if comp:
                     if self.peer_residual[j] is None:
                         raise RuntimeError("this workload was built without peer residuals")

@@ -28,7 +28,9 @@ def declared_functions():
 def test_header_declares_the_named_entry_points():
     names = declared_functions()
     for must in ("cdsgd_quantize_pack", "cdsgd_decode_sum", "cdsgd_update", "cdsgd_step_fused",
-                 "cdsgd_plan_create", "cdsgd_plan_destroy", "cdsgd_packed_words", "cdsgd_status_string"):
+                 "cdsgd_plan_create", "cdsgd_plan_destroy", "cdsgd_packed_words", "cdsgd_status_string",
+                 "cdsgd_plan_bind_full_grads", "cdsgd_step_warmup", "cdsgd_trainer_create",
+                 "cdsgd_trainer_step", "cdsgd_trainer_iteration", "cdsgd_trainer_destroy"):
         assert must in names
 
 
@@ -146,6 +148,34 @@ def test_plan_and_step_argument_errors(L):
     assert step(fake, -1, 4, 0.5, 0.1, 0.1, None) == ERR_PARAM
     assert step(fake, 1, 4, 0.0, 0.1, 0.1, None) == ERR_PARAM
     assert step(fake, 1, 4, 0.5, float("nan"), 0.1, None) == ERR_PARAM
+
+
+def test_warmup_and_trainer_argument_errors(L):
+    from paper_2106_10796_amd.binding import ERR_NULL, ERR_PARAM, OK
+    fake = ctypes.c_void_p(A)   # never dereferenced: parameter checks come first
+    w = L.cdsgd_step_warmup
+    assert w(None, 0, 2, 0.1, 0.1, None) == ERR_NULL
+    assert w(fake, -1, 2, 0.1, 0.1, None) == ERR_PARAM
+    assert w(fake, 3, 2, 0.1, 0.1, None) == ERR_PARAM
+    assert w(fake, 0, -1, 0.1, 0.1, None) == ERR_PARAM
+    assert w(fake, 0, 2, float("nan"), 0.1, None) == ERR_PARAM
+    out = ctypes.c_void_p()
+    c = L.cdsgd_trainer_create
+    assert c(None, 2, 4, 0.5, 0.1, 0.1, ctypes.byref(out)) == ERR_NULL
+    assert c(fake, 2, 4, 0.5, 0.1, 0.1, None) == ERR_NULL
+    assert c(fake, -1, 4, 0.5, 0.1, 0.1, ctypes.byref(out)) == ERR_PARAM
+    assert c(fake, 2, 0, 0.5, 0.1, 0.1, ctypes.byref(out)) == ERR_PARAM
+    assert c(fake, 2, 4, -0.5, 0.1, 0.1, ctypes.byref(out)) == ERR_PARAM
+    assert c(fake, 2, 4, 0.5, float("inf"), 0.1, ctypes.byref(out)) == ERR_PARAM
+    assert out.value is None
+    assert L.cdsgd_trainer_step(None, None, None) == ERR_NULL
+    assert L.cdsgd_trainer_iteration(None) == -1
+    assert L.cdsgd_trainer_destroy(None) == OK
+    assert L.cdsgd_plan_bind_full_grads(None, None) == ERR_NULL
+    # a trainer is host state only: create / query / destroy work without a GPU
+    assert c(fake, 2, 4, 0.5, 0.1, 0.1, ctypes.byref(out)) == OK
+    assert L.cdsgd_trainer_iteration(out) == 0
+    assert L.cdsgd_trainer_destroy(out) == OK
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):

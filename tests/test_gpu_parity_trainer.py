@@ -1,0 +1,89 @@
+"""GPU parity of Alg. 1 end to end (WARMUP passes, then FormalTraining) through
+cdsgd_trainer_step, against the oracle's trainer, every iteration, on ragged layer lists.
+Both sources of the 32-bit aggregate are covered: summed in the kernel from the N gradients
+(cdsgd_plan_bind_full_grads) and read from agg_full."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import assert_bits_equal, assert_close
+
+pytestmark = pytest.mark.gpu
+
+SIZES = [4096, 4097, 1000, 64, 10, 36864, 20011, 1]
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2106_10796_amd as pkg
+    from paper_2106_10796_amd import runner, synth
+    pkg.binding.lib()
+    assert torch.cuda.is_available()
+    return pkg, runner, synth
+
+
+@pytest.mark.parametrize("full_grads", [True, False], ids=["kernel_sum", "agg_full"])
+@pytest.mark.parametrize("warmup_n,N,self_rank,k,base", [
+    (0, 4, 0, 3, "c2_resnet20"), (1, 8, 5, 4, "c2_resnet20"), (3, 16, 15, 2, "c3_resnet50"),
+    (2, 1, 0, 3, "c1_single"), (2, 3, 1, 1, "c5_flat4g")])
+def test_trainer_matches_oracle(P, oracle, full_grads, warmup_n, N, self_rank, k, base):
+    pkg, runner, synth = P
+    cfg = synth.scaled(synth.config(base), SIZES, "_trainer")
+    cfg.num_workers, cfg.k = N, k
+    wl = runner.Workload(cfg, dense=True, self_rank=self_rank, full_grads=full_grads)
+    lr_l, lr_g = 0.4, 0.1
+    trainer = pkg.Trainer(wl.plan, warmup_n, k, cfg.threshold, lr_l, lr_g)
+    blocks = [(i, 0, n) for i, n in enumerate(cfg.sizes)]
+    sims = [oracle.TrainerSimulation(wl.view(wl.w_global, i).cpu().numpy(), N, warmup_n, k, cfg.threshold,
+                                     lr_l, lr_g, self_rank) for i in range(cfg.num_tensors)]
+    kinds = []
+    for it in range(warmup_n + 1 + 2 * k + 1):
+        count = it - warmup_n - 1
+        comp = it > warmup_n and count % k != 0
+        cap = wl.prepare_step(it, capture=blocks, compressed=comp)
+        loc_before = wl.w_local.clone()
+        res_before = wl.residual.clone()
+        assert trainer.iteration == it
+        kind = trainer.step()
+        torch.cuda.synchronize()
+        kinds.append(kind)
+        for i in range(cfg.num_tensors):
+            mode, agg, words = sims[i].step([cap[j][i] for j in range(N)])
+            assert mode == kind
+            tag = "iteration %d tensor %d (n=%d)" % (it, i, cfg.sizes[i])
+            if mode == 1:
+                assert_bits_equal(wl.pview(wl.packed_self, i).cpu().numpy(), words[self_rank].view(np.int32),
+                                  "packed " + tag)
+            else:
+                assert torch.equal(wl.view(wl.residual, i), wl.view(res_before, i)), "residual touched " + tag
+            assert_bits_equal(wl.view(wl.residual, i).cpu().numpy(), sims[i].residual[self_rank], "residual " + tag)
+            gw, gl = wl.view(wl.w_global, i).cpu().numpy(), wl.view(wl.w_local, i).cpu().numpy()
+            assert_close(gw, sims[i].w_global, "w_global " + tag)
+            assert_close(gl, sims[i].w_local, "w_local " + tag)
+            assert_bits_equal(gw, sims[i].w_global, "w_global bits " + tag)
+            assert_bits_equal(gl, sims[i].w_local, "w_local bits " + tag)
+            if mode == 0 and it < warmup_n - 1:
+                assert torch.equal(wl.view(wl.w_local, i), wl.view(loc_before, i)), "w_local written early " + tag
+    expect = [0] * (warmup_n + 1) + [2 if c % k == 0 else 1 for c in range(2 * k + 1)]
+    assert kinds == expect
+    trainer.destroy()
+    wl.destroy()
+
+
+def test_full_pass_needs_an_aggregate(P):
+    """A plan with neither agg_full nor bound gradients cannot run a correction or warm-up pass."""
+    pkg, runner, synth = P
+    B = pkg.binding
+    n = 100
+    mk = lambda: torch.zeros(n, device="cuda")
+    t = dict(w_global=mk(), w_local=mk(), residual=mk(), grad=mk(), packed_self=B.new_packed(n))
+    plan = B.Plan([t], [None, [B.new_packed(n)]], 2, 0)
+    with pytest.raises(B.CdsgdError) as e:
+        plan.step(0, 4, 0.5, 0.1, 0.1)
+    assert e.value.status == B.ERR_NULL
+    with pytest.raises(B.CdsgdError) as e:
+        plan.step_warmup(0, 2, 0.1, 0.1)
+    assert e.value.status == B.ERR_NULL
+    plan.step(1, 4, 0.5, 0.1, 0.1)      # compressed passes do not need it
+    torch.cuda.synchronize()
+    plan.destroy()
