@@ -80,6 +80,11 @@ def time_workload(name, steps, warmup, want_correction=True, want_unfused=False)
         run(_compressed_steps(cfg.k, 1), wl.unfused_step)
         ms_u = run(_compressed_steps(cfg.k, max(2, steps // 4)), wl.unfused_step)
         out["threecall_ms_per_step"] = ms_u
+        # delta of the paper's model: the worker-side compression alone (quantise + pack, one flat call)
+        from paper_2106_10796_amd import binding
+        qp = lambda s: binding.cdsgd_quantize_pack(wl.grad, wl.residual, wl.packed_self, cfg.threshold)
+        run([1], qp)
+        out["quantize_pack_ms"] = run([1] * max(3, steps // 4), qp)
     return out, wl
 
 
@@ -106,6 +111,83 @@ def time_correction_sum(name, steps, warmup):
     wl.destroy()
     return {"ms_per_step": ms, "bytes_per_element": bpe, "gbs": cfg.elements * bpe / (ms * 1e-3) / 1e9,
             "frac_hbm_peak": cfg.elements * bpe / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+
+def overlap_demo(name, iters=12):
+    """Overhead hiding on one GPU (Sec. 3.2.2, Fig. 5): the next forward pass only needs the local
+    weights.  Fused form: forward stand-in waits for the whole fused step.  Split form: stream L
+    runs cdsgd_step_local and then the forward stand-in, stream G runs cdsgd_step_global behind an
+    event; the next iteration's local update waits for G.  The stand-in is a compute-bound bf16
+    matrix product; both streams have the default priority."""
+    import torch
+    from paper_2106_10796_amd import runner, synth
+    cfg = synth.config(name)
+    wl = runner.Workload(cfg)
+    wl.prepare_step(1)
+    wl.peer_residual = [None] * cfg.num_workers
+    wl._scratch = None
+    torch.cuda.empty_cache()
+    M = 8192
+    x = torch.randn(M, M, device="cuda", dtype=torch.bfloat16)
+    y = torch.randn(M, M, device="cuda", dtype=torch.bfloat16)
+    z = torch.empty(M, M, device="cuda", dtype=torch.bfloat16)
+    main = torch.cuda.current_stream()
+    side = torch.cuda.Stream()
+    steps = _compressed_steps(cfg.k, iters)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(main)
+        fn()
+        e1.record(main)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    def only(fn):
+        return lambda: [fn(s) for s in steps]
+
+    def fused_then_forward():
+        for s in steps:
+            wl.fused_step(s)
+            torch.mm(x, y, out=z)
+
+    def split_serial():
+        for s in steps:
+            wl.plan.step_local(cfg.lr)
+            torch.mm(x, y, out=z)
+            wl.plan.step_global(s, cfg.k, cfg.threshold, cfg.lr)
+
+    def split_overlapped():
+        g_done = None
+        for s in steps:
+            if g_done is not None:
+                main.wait_event(g_done)            # next local update reads the new global weights
+            wl.plan.step_local(cfg.lr)
+            l_done = torch.cuda.Event()
+            l_done.record(main)
+            torch.mm(x, y, out=z)                  # forward stand-in, needs only w_local
+            with torch.cuda.stream(side):
+                side.wait_event(l_done)
+                wl.plan.step_global(s, cfg.k, cfg.threshold, cfg.lr)
+                g_done = torch.cuda.Event()
+                g_done.record(side)
+        main.wait_event(g_done)
+
+    out = {
+        "workload": name, "forward_stand_in": "bf16 %dx%dx%d matrix product" % (M, M, M),
+        "ms_fused_step": timed(only(wl.fused_step)),
+        "ms_step_local": timed(only(lambda s: wl.plan.step_local(cfg.lr))),
+        "ms_step_global": timed(only(lambda s: wl.plan.step_global(s, cfg.k, cfg.threshold, cfg.lr))),
+        "ms_forward_stand_in": timed(only(lambda s: torch.mm(x, y, out=z))),
+        "ms_iter_fused_then_forward": timed(fused_then_forward),
+        "ms_iter_split_one_stream": timed(split_serial),
+        "ms_iter_split_two_streams": timed(split_overlapped),
+    }
+    out["forward_can_start_after_ms"] = {"fused": out["ms_fused_step"], "split": out["ms_step_local"]}
+    wl.destroy()
+    return out
 
 
 def cpu_baseline(wl, target_seconds=12.0):
@@ -213,6 +295,20 @@ def main():
         extra["correction_with_kernel_sum_" + args.workload] = time_correction_sum(
             args.workload, max(3, args.steps // 4), max(1, args.warmup // 2))
         torch.cuda.empty_cache()
+        extra["overlap_demo"] = overlap_demo(args.workload)
+        torch.cuda.empty_cache()
+        # the paper's time model (Sec. 3.3) fed with the measured delta; tau and the wire are assumptions
+        n_el, k = head["elements"], head["k"]
+        wire = 56e9 / 8                                   # the paper's 56 Gbps InfiniBand, bytes/s
+        assume = {"tau_ms": 100.0, "phi_ms": 2 * 4 * n_el / wire * 1e3,           # push fp32 + pull fp32
+                  "psi_ms": (n_el / 4 + 4 * n_el) / wire * 1e3,                    # push 2-bit + pull fp32
+                  "delta_ms": head["quantize_pack_ms"], "k": k}
+        extra["time_model"] = {
+            "assumptions": "tau = 100 ms (not measured: no FP/BP here); parameter-server wire at 56 Gbps: "
+                           "phi = 8n B, psi = (n/4 + 4n) B; delta = measured cdsgd_quantize_pack time",
+            "inputs": assume,
+            "period_mean": binding.cdsgd_cost_period_mean(assume["tau_ms"], assume["phi_ms"], assume["psi_ms"],
+                                                          assume["delta_ms"], k)}
         for name in ("c3_resnet50", "c5_flat4g"):
             if name == args.workload:
                 continue

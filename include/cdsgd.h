@@ -154,6 +154,26 @@ int cdsgd_step_fused(cdsgd_plan *plan, long step, int k, float threshold, float 
                      float lr_global, void *hip_stream);
 
 /*
+ * Split form of cdsgd_step_fused, for overlapping the next forward pass with the
+ * rest of the step (Sec. 3.2.2: once the local weights are updated the next
+ * iteration can start, whatever quantisation and communication still have to do).
+ *   cdsgd_step_local   eq. 11 only, for every tensor: w_local = W - lr_local * grad.
+ *                      Reads w_global and grad, writes w_local.
+ *   cdsgd_step_global  everything else of the same pass (quantise + pack, decode and
+ *                      sum, eq. 10; or the correction branch): same arguments and
+ *                      errors as cdsgd_step_fused without lr_local; w_local is not
+ *                      touched.  It overwrites w_global, which cdsgd_step_local reads:
+ *                      the caller must order it after the cdsgd_step_local of the same
+ *                      pass (same stream, or an event).
+ * Run in that order the two calls leave exactly what cdsgd_step_fused leaves, at
+ * the price of reading grad and w_global twice (36 + N/4 instead of 24 + N/4 bytes
+ * per element on a compressed pass).
+ */
+int cdsgd_step_local(cdsgd_plan *plan, float lr_local, void *hip_stream);
+int cdsgd_step_global(cdsgd_plan *plan, long step, int k, float threshold, float lr_global,
+                      void *hip_stream);
+
+/*
  * Let correction and warm-up passes sum the workers' 32-bit gradients themselves
  * (Alg. 1, else-branch and WARMUP; the sum of eq. 1) instead of reading agg_full:
  * one launch then reads W and the N gradients and writes W and W_loc.

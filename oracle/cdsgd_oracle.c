@@ -29,6 +29,8 @@
  *   oracle_step          Alg. 1, FormalTraining, one pass of the while loop
  *   oracle_warmup_step   Alg. 1, WARMUP, one pass of the while loop
  *   oracle_trainer_step  Alg. 1 as a whole: WARMUP for i = 0..n, then FormalTraining
+ *   oracle_cost_model    eq. 2, 4, 5, 6, 7 (iteration times); the savings are the
+ *                        differences T_loc - T_cd and T_bit - T_cd that Sec. 3.3 defines
  *
  * Every function here is pinned by tests/test_oracle_pins.py (hand-unrolled
  * recurrence, closed forms, invariants, brute force on tiny inputs).  The four
@@ -205,4 +207,24 @@ int oracle_trainer_step(float *w_global, float *w_local, float *const *residual,
                        iter - warmup_n - 1, k, t, lr_local, lr_global)
                ? 1
                : 2;
+}
+
+/* The paper's time model, from the definitions only (in double: these are
+ * modelled times, not fp32 training state).  out[0..6] = T_ssgd (eq. 2), T_loc
+ * (eq. 4), T_bit (eq. 5), phi_cd (eq. 6), T_cd (eq. 7), T_loc - T_cd, T_bit - T_cd
+ * (the two savings as Sec. 3.3 defines them, not the case tables of eq. 8/9). */
+void oracle_cost_model(double tau, double phi, double psi, double delta, int k, long i, double *out)
+{
+    double t_ssgd = tau + phi;
+    double t_loc = tau > phi ? tau : phi;
+    double t_bit = tau + delta + psi;
+    double phi_cd = (i % k != 0) ? delta + psi : phi;
+    double t_cd = tau > phi_cd ? tau : phi_cd;
+    out[0] = t_ssgd;
+    out[1] = t_loc;
+    out[2] = t_bit;
+    out[3] = phi_cd;
+    out[4] = t_cd;
+    out[5] = t_loc - t_cd;
+    out[6] = t_bit - t_cd;
 }

@@ -53,6 +53,9 @@ def lib():
                                           ctypes.POINTER(_u32p), _f32p, _u8p, ctypes.c_size_t, ctypes.c_int,
                                           ctypes.c_int, ctypes.c_long, ctypes.c_long, ctypes.c_int,
                                           ctypes.c_float, ctypes.c_float, ctypes.c_float]
+        L.oracle_cost_model.restype = None
+        L.oracle_cost_model.argtypes = [ctypes.c_double] * 4 + [ctypes.c_int, ctypes.c_long,
+                                                                ctypes.POINTER(ctypes.c_double)]
         _lib = L
     return _lib
 
@@ -138,6 +141,14 @@ def update(w_global, w_local, grad_local, agg, lr_local, lr_global, num_workers)
             _chk(a, np.float32, n)
     lib().oracle_update(_p(w_global, _f32p), _p(w_local, _f32p), _p(grad_local, _f32p), _p(agg, _f32p),
                         n, float(lr_local), float(lr_global), int(num_workers))
+
+
+def cost_model(tau, phi, psi, delta, k, i):
+    """dict of the iteration times of eq. 2, 4, 5, 6, 7 and the two savings as differences."""
+    out = (ctypes.c_double * 7)()
+    lib().oracle_cost_model(float(tau), float(phi), float(psi), float(delta), int(k), int(i), out)
+    names = ("t_ssgd", "t_loc", "t_bit", "phi_cd", "t_cd", "save_vs_loc", "save_vs_bit")
+    return dict(zip(names, list(out)))
 
 
 class Simulation:

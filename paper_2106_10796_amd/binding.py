@@ -31,6 +31,21 @@ class cdsgd_tensor(ctypes.Structure):
                 ("n", ctypes.c_size_t)]
 
 
+class cdsgd_cost_params(ctypes.Structure):
+    _fields_ = [("tau", ctypes.c_double), ("phi", ctypes.c_double), ("psi", ctypes.c_double),
+                ("delta", ctypes.c_double), ("k", ctypes.c_int)]
+
+
+class cdsgd_cost(ctypes.Structure):
+    _fields_ = [("t_ssgd", ctypes.c_double), ("t_loc", ctypes.c_double), ("t_bit", ctypes.c_double),
+                ("phi_cd", ctypes.c_double), ("t_cd", ctypes.c_double), ("save_vs_bit", ctypes.c_double),
+                ("save_vs_loc", ctypes.c_double), ("case_bit", ctypes.c_int), ("case_loc", ctypes.c_int),
+                ("eq9_assumption_holds", ctypes.c_int)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
 _lib = None
 
 
@@ -60,6 +75,10 @@ def lib():
         L.cdsgd_plan_destroy.argtypes = [vp]
         L.cdsgd_step_fused.restype = i
         L.cdsgd_step_fused.argtypes = [vp, ctypes.c_long, i, f, f, f, vp]
+        L.cdsgd_step_local.restype = i
+        L.cdsgd_step_local.argtypes = [vp, f, vp]
+        L.cdsgd_step_global.restype = i
+        L.cdsgd_step_global.argtypes = [vp, ctypes.c_long, i, f, f, vp]
         L.cdsgd_plan_bind_full_grads.restype = i
         L.cdsgd_plan_bind_full_grads.argtypes = [vp, ctypes.POINTER(ctypes.POINTER(vp))]
         L.cdsgd_step_warmup.restype = i
@@ -72,6 +91,11 @@ def lib():
         L.cdsgd_trainer_iteration.argtypes = [vp]
         L.cdsgd_trainer_destroy.restype = i
         L.cdsgd_trainer_destroy.argtypes = [vp]
+        L.cdsgd_cost_iteration.restype = i
+        L.cdsgd_cost_iteration.argtypes = [ctypes.POINTER(cdsgd_cost_params), ctypes.c_long,
+                                           ctypes.POINTER(cdsgd_cost)]
+        L.cdsgd_cost_period_mean.restype = i
+        L.cdsgd_cost_period_mean.argtypes = [ctypes.POINTER(cdsgd_cost_params), ctypes.POINTER(cdsgd_cost)]
         _lib = L
     return _lib
 
@@ -136,6 +160,20 @@ def cdsgd_update(w_global, w_local, grad_local, agg, lr_local, lr_global, num_wo
     _check(st, "cdsgd_update")
 
 
+def cdsgd_cost_iteration(tau, phi, psi, delta, k, i) -> dict:
+    p = cdsgd_cost_params(float(tau), float(phi), float(psi), float(delta), int(k))
+    out = cdsgd_cost()
+    _check(lib().cdsgd_cost_iteration(ctypes.byref(p), int(i), ctypes.byref(out)), "cdsgd_cost_iteration")
+    return out.as_dict()
+
+
+def cdsgd_cost_period_mean(tau, phi, psi, delta, k) -> dict:
+    p = cdsgd_cost_params(float(tau), float(phi), float(psi), float(delta), int(k))
+    out = cdsgd_cost()
+    _check(lib().cdsgd_cost_period_mean(ctypes.byref(p), ctypes.byref(out)), "cdsgd_cost_period_mean")
+    return out.as_dict()
+
+
 class Plan:
     """A fused-step plan over a layer list (cdsgd_plan_create / cdsgd_step_fused / cdsgd_plan_destroy).
 
@@ -184,6 +222,14 @@ class Plan:
         st = lib().cdsgd_step_fused(self._handle, int(step), int(k), float(threshold), float(lr_local),
                                     float(lr_global), _stream())
         _check(st, "cdsgd_step_fused")
+
+    def step_local(self, lr_local):
+        st = lib().cdsgd_step_local(self._handle, float(lr_local), _stream())
+        _check(st, "cdsgd_step_local")
+
+    def step_global(self, step, k, threshold, lr_global):
+        st = lib().cdsgd_step_global(self._handle, int(step), int(k), float(threshold), float(lr_global), _stream())
+        _check(st, "cdsgd_step_global")
 
     def bind_full_grads(self, peer_grads):
         """peer_grads[j][i]: worker j's fp32 gradient of tensor i; entry self_rank may be None

@@ -7,6 +7,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 SRC = os.path.join(PKG, "csrc", "cdsgd.hip")
+SRC_HOST = [os.path.join(PKG, "csrc", "cdsgd_cost_model.cpp")]   # host-only parts of the library
 INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(PKG, "libcdsgd.so")
 
@@ -30,7 +31,7 @@ def hipcc_path() -> str:
 
 def build(extra_flags=(), out=LIB, verbose=False) -> str:
     tmp = out + ".tmp%d" % os.getpid()
-    cmd = [hipcc_path(), *HIPCC_FLAGS, *extra_flags, "-I", INCLUDE, SRC, "-o", tmp]
+    cmd = [hipcc_path(), *HIPCC_FLAGS, *extra_flags, "-I", INCLUDE, SRC, *SRC_HOST, "-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

@@ -48,6 +48,9 @@
 #ifndef CDSGD_NT_CODES
 #define CDSGD_NT_CODES 0
 #endif
+#ifndef CDSGD_FULL_BATCH
+#define CDSGD_FULL_BATCH 8
+#endif
 #ifndef CDSGD_XCD_REMAP
 #define CDSGD_XCD_REMAP 0
 #endif
@@ -447,7 +450,7 @@ __global__ __launch_bounds__(CDSGD_BLOCK) void k_update(float *__restrict__ wg, 
 }
 
 // Fused compressed step (a1-a6) for one chunk of one tensor.
-template <bool G, bool POW2>
+template <bool G, bool POW2, bool WRITE_LOCAL>
 __device__ __forceinline__ void fused_chunk(const TensorDesc &d, const uint8_t *const *__restrict__ peers,
                                             int num_peers, int self, size_t quad0, unsigned rem_elems,
                                             unsigned rem_bytes, float t, float lr_local, float scale,
@@ -509,13 +512,14 @@ __device__ __forceinline__ void fused_chunk(const TensorDesc &d, const uint8_t *
             vl[c] = __builtin_fmaf(-lr_local, g[j][c], w[j][c]);
             vg[c] = __builtin_fmaf(-scale, agg[j][c], w[j][c]);
         }
-        st4g<G>(wl, qi, cnt[j], vl);
+        if (WRITE_LOCAL) st4g<G>(wl, qi, cnt[j], vl);
         st4g<G>(wg, qi, cnt[j], vg);
     }
 }
 
 // peers: [num_tensors][num_peers] pointers, this worker's own row left out.
-template <bool POW2>
+// WRITE_LOCAL = false leaves eq. 11 to a separate, earlier launch (k_plan_local).
+template <bool POW2, bool WRITE_LOCAL>
 __global__ __launch_bounds__(CDSGD_BLOCK) void k_fused_compressed(const TensorDesc *__restrict__ tensors,
                                                                   const ChunkRef *__restrict__ chunks,
                                                                   const uint8_t *const *__restrict__ peers,
@@ -527,10 +531,25 @@ __global__ __launch_bounds__(CDSGD_BLOCK) void k_fused_compressed(const TensorDe
     const size_t quad0 = (size_t)cr.chunk * kChunkQuads;
     const uint8_t *const *tp = peers + (size_t)cr.tensor * (size_t)num_peers;
     if (cr.chunk < d.ext.full_chunks)
-        fused_chunk<false, POW2>(d, tp, num_peers, self, quad0, kChunkElems, kChunkQuads, t, lr_local, scale, bias_t);
+        fused_chunk<false, POW2, WRITE_LOCAL>(d, tp, num_peers, self, quad0, kChunkElems, kChunkQuads, t, lr_local,
+                                              scale, bias_t);
     else
-        fused_chunk<true, POW2>(d, tp, num_peers, self, quad0, d.ext.tail_elems, d.ext.tail_bytes, t, lr_local,
+        fused_chunk<true, POW2, WRITE_LOCAL>(d, tp, num_peers, self, quad0, d.ext.tail_elems, d.ext.tail_bytes, t, lr_local,
                                 scale, bias_t);
+}
+
+// eq. 11 alone over the layer list: w_local = W - lr_local * g (reads W, g; writes w_local).
+__global__ __launch_bounds__(CDSGD_BLOCK) void k_plan_local(const TensorDesc *__restrict__ tensors,
+                                                            const ChunkRef *__restrict__ chunks, float lr_local)
+{
+    const ChunkRef cr = chunks[chunk_slot()];
+    const TensorDesc d = tensors[cr.tensor];
+    const size_t quad0 = (size_t)cr.chunk * kChunkQuads;
+    float *wg = d.w_global + 4 * quad0;
+    float *wl = d.w_local + 4 * quad0;
+    const float *grad = d.grad + 4 * quad0;
+    if (cr.chunk < d.ext.full_chunks) update_chunk<false, true, false>(wg, wl, grad, nullptr, kChunkElems, lr_local, 0.0f);
+    else update_chunk<true, true, false>(wg, wl, grad, nullptr, d.ext.tail_elems, lr_local, 0.0f);
 }
 
 // Passes that use the workers' 32-bit gradients (Alg. 1: WARMUP passes and the
@@ -543,6 +562,7 @@ __global__ __launch_bounds__(CDSGD_BLOCK) void k_fused_compressed(const TensorDe
 //          kLocalCopy: w_local = new global weight   (WARMUP, i == n-1, the copy after the pull)
 //          kLocalRule: w_local = W - lr_local * g    (WARMUP, i == n; correction passes; eq. 11)
 constexpr int kLocalNone = 0, kLocalCopy = 1, kLocalRule = 2;
+constexpr int kFullBatch = CDSGD_FULL_BATCH;  // peers' gradients in flight together
 
 template <bool G, bool SUM, int LOCAL>
 __device__ __forceinline__ void full_chunk(const TensorDesc &d, const float *const *__restrict__ pg,
@@ -567,15 +587,15 @@ __device__ __forceinline__ void full_chunk(const TensorDesc &d, const float *con
     if (SUM) {
         auto add_range = [&](int p_begin, int p_end) {
             int p = p_begin;
-            for (; p + 4 <= p_end; p += 4) {
-                f4 v[4][kQpl];
+            for (; p + kFullBatch <= p_end; p += kFullBatch) {
+                f4 v[kFullBatch][kQpl];
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < kFullBatch; ++i)
 #pragma unroll
                     for (unsigned j = 0; j < kQpl; ++j)
                         v[i][j] = ld4g<G>(pg[p + i] + 4 * quad0, j * kBlock + tid, cnt[j]);
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < kFullBatch; ++i)
 #pragma unroll
                     for (unsigned j = 0; j < kQpl; ++j) a[j] = a[j] + v[i][j];
             }
@@ -906,28 +926,57 @@ int cdsgd_plan_destroy(cdsgd_plan *plan)
     return rc;
 }
 
-int cdsgd_step_fused(cdsgd_plan *plan, long step, int k, float threshold, float lr_local, float lr_global,
-                     void *hip_stream)
+namespace {
+
+// One pass of FormalTraining's loop; with_local = false leaves eq. 11 out (split form).
+int launch_formal_pass(cdsgd_plan *plan, long step, int k, float threshold, float lr_local, float lr_global,
+                       bool with_local, void *hip_stream)
 {
     if (!plan) return CDSGD_ERR_NULL;
     if (k < 1 || step < 0 || !good_threshold(threshold) || !std::isfinite(lr_local) || !std::isfinite(lr_global))
         return CDSGD_ERR_PARAM;
     const bool compressed = (step % k) != 0;
-    if (!compressed) return launch_full_pass(plan, kLocalRule, lr_local, lr_global, hip_stream);
+    if (!compressed)
+        return launch_full_pass(plan, with_local ? kLocalRule : kLocalNone, lr_local, lr_global, hip_stream);
     const float scale = lr_global / (float)plan->num_workers;
     hipStream_t s = (hipStream_t)hip_stream;
     const dim3 grid(plan->num_chunks), block(kBlock);
-    if (compressed) {
-        const int num_peers = plan->num_workers - 1;
-        const float bias_t = -(2.0f * (float)plan->num_workers) * threshold;
-        if (is_pow2_threshold(threshold))
-            hipLaunchKernelGGL(k_fused_compressed<true>, grid, block, 0, s, plan->tensors, plan->chunks,
-                               plan->peers, num_peers, plan->self, threshold, lr_local, scale, bias_t);
-        else
-            hipLaunchKernelGGL(k_fused_compressed<false>, grid, block, 0, s, plan->tensors, plan->chunks,
-                               plan->peers, num_peers, plan->self, threshold, lr_local, scale, bias_t);
+    const int num_peers = plan->num_workers - 1;
+    const float bias_t = -(2.0f * (float)plan->num_workers) * threshold;
+#define CDSGD_LAUNCH_COMPRESSED(POW2, LOCAL)                                                                  \
+    hipLaunchKernelGGL((k_fused_compressed<POW2, LOCAL>), grid, block, 0, s, plan->tensors, plan->chunks,      \
+                       plan->peers, num_peers, plan->self, threshold, lr_local, scale, bias_t)
+    if (is_pow2_threshold(threshold)) {
+        if (with_local) CDSGD_LAUNCH_COMPRESSED(true, true);
+        else CDSGD_LAUNCH_COMPRESSED(true, false);
+    } else {
+        if (with_local) CDSGD_LAUNCH_COMPRESSED(false, true);
+        else CDSGD_LAUNCH_COMPRESSED(false, false);
     }
+#undef CDSGD_LAUNCH_COMPRESSED
     return launch_status();
+}
+
+}  // namespace
+
+int cdsgd_step_fused(cdsgd_plan *plan, long step, int k, float threshold, float lr_local, float lr_global,
+                     void *hip_stream)
+{
+    return launch_formal_pass(plan, step, k, threshold, lr_local, lr_global, true, hip_stream);
+}
+
+int cdsgd_step_local(cdsgd_plan *plan, float lr_local, void *hip_stream)
+{
+    if (!plan) return CDSGD_ERR_NULL;
+    if (!std::isfinite(lr_local)) return CDSGD_ERR_PARAM;
+    hipLaunchKernelGGL(k_plan_local, dim3(plan->num_chunks), dim3(kBlock), 0, (hipStream_t)hip_stream,
+                       plan->tensors, plan->chunks, lr_local);
+    return launch_status();
+}
+
+int cdsgd_step_global(cdsgd_plan *plan, long step, int k, float threshold, float lr_global, void *hip_stream)
+{
+    return launch_formal_pass(plan, step, k, threshold, 0.0f, lr_global, false, hip_stream);
 }
 
 int cdsgd_plan_bind_full_grads(cdsgd_plan *plan, const float *const *const *peer_grads)

@@ -8,7 +8,7 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "cdsgd.h")
+HEADERS = [os.path.join(ROOT, "include", "cdsgd.h"), os.path.join(ROOT, "include", "cdsgd_cost_model.h")]
 
 
 @pytest.fixture(scope="module")
@@ -20,7 +20,7 @@ def L():
 
 
 def declared_functions():
-    src = open(HEADER).read()
+    src = "\n".join(open(h).read() for h in HEADERS)
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     return sorted(set(re.findall(r"\b(cdsgd_[a-z_]+)\s*\(", src)))
 
@@ -30,7 +30,8 @@ def test_header_declares_the_named_entry_points():
     for must in ("cdsgd_quantize_pack", "cdsgd_decode_sum", "cdsgd_update", "cdsgd_step_fused",
                  "cdsgd_plan_create", "cdsgd_plan_destroy", "cdsgd_packed_words", "cdsgd_status_string",
                  "cdsgd_plan_bind_full_grads", "cdsgd_step_warmup", "cdsgd_trainer_create",
-                 "cdsgd_trainer_step", "cdsgd_trainer_iteration", "cdsgd_trainer_destroy"):
+                 "cdsgd_trainer_step", "cdsgd_trainer_iteration", "cdsgd_trainer_destroy",
+                 "cdsgd_step_local", "cdsgd_step_global", "cdsgd_cost_iteration", "cdsgd_cost_period_mean"):
         assert must in names
 
 
@@ -172,6 +173,11 @@ def test_warmup_and_trainer_argument_errors(L):
     assert L.cdsgd_trainer_iteration(None) == -1
     assert L.cdsgd_trainer_destroy(None) == OK
     assert L.cdsgd_plan_bind_full_grads(None, None) == ERR_NULL
+    assert L.cdsgd_step_local(None, 0.1, None) == ERR_NULL
+    assert L.cdsgd_step_local(fake, float("nan"), None) == ERR_PARAM
+    assert L.cdsgd_step_global(None, 1, 4, 0.5, 0.1, None) == ERR_NULL
+    assert L.cdsgd_step_global(fake, 1, 0, 0.5, 0.1, None) == ERR_PARAM
+    assert L.cdsgd_step_global(fake, 1, 4, 0.5, float("inf"), None) == ERR_PARAM
     # a trainer is host state only: create / query / destroy work without a GPU
     assert c(fake, 2, 4, 0.5, 0.1, 0.1, ctypes.byref(out)) == OK
     assert L.cdsgd_trainer_iteration(out) == 0

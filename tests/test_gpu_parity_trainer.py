@@ -87,3 +87,42 @@ def test_full_pass_needs_an_aggregate(P):
     plan.step(1, 4, 0.5, 0.1, 0.1)      # compressed passes do not need it
     torch.cuda.synchronize()
     plan.destroy()
+
+
+@pytest.mark.parametrize("t_pow2", [True, False], ids=["t0.5", "t0.05"])
+def test_split_step_equals_fused(P, oracle, t_pow2):
+    """cdsgd_step_local then cdsgd_step_global (on a second stream, ordered by an event)
+    leave bit for bit what cdsgd_step_fused leaves, on compressed and correction passes;
+    cdsgd_step_local alone matches eq. 11 of the oracle and leaves w_global alone."""
+    pkg, runner, synth = P
+    cfg = synth.scaled(synth.config("c2_resnet20" if t_pow2 else "c5_flat4g"), SIZES, "_split")
+    cfg.num_workers, cfg.k = 8, 3
+    a = runner.Workload(cfg, dense=True, self_rank=3)     # fused
+    b = runner.Workload(cfg, dense=True, self_rank=3)     # split
+    side = torch.cuda.Stream()                            # default priority
+    main = torch.cuda.current_stream()
+    for s in range(2 * cfg.k + 1):
+        a.prepare_step(s)
+        b.prepare_step(s)
+        a.fused_step(s)
+        wg_before = b.w_global.clone()
+        b.plan.step_local(cfg.lr)
+        local_done = torch.cuda.Event()
+        local_done.record(main)
+        torch.cuda.synchronize()
+        # eq. 11 alone, against the oracle
+        for i in range(cfg.num_tensors):
+            W = b.view(wg_before, i).cpu().numpy()
+            L = np.zeros_like(W)
+            oracle.update(W, L, b.view(b.grad, i).cpu().numpy(), None, cfg.lr, cfg.lr, cfg.num_workers)
+            assert_bits_equal(b.view(b.w_local, i).cpu().numpy(), L, "w_local after step_local, step %d tensor %d" % (s, i))
+        assert torch.equal(b.w_global, wg_before)
+        with torch.cuda.stream(side):
+            side.wait_event(local_done)
+            b.plan.step_global(s, cfg.k, cfg.threshold, cfg.lr)
+        torch.cuda.synchronize()
+        for key in ("w_global", "w_local", "residual", "packed_self"):
+            x, y = getattr(a, key), getattr(b, key)
+            assert torch.equal(x.view(torch.int32), y.view(torch.int32)), "%s differs at step %d" % (key, s)
+    a.destroy()
+    b.destroy()

@@ -49,6 +49,11 @@ MUTANTS = [
      "w_local[e] = fmaf(-lr_global, grad[self][e], w_local[e]);"),
     ("warmup_one_pass_short", "if (iter <= warmup_n) {", "if (iter < warmup_n) {"),
     ("formal_count_not_reset", "iter - warmup_n - 1, k, t,", "iter, k, t,"),
+    ("cost_correction_case_swapped", "double phi_cd = (i % k != 0) ? delta + psi : phi;",
+     "double phi_cd = (i % k == 0) ? delta + psi : phi;"),
+    ("cost_local_is_sum", "double t_loc = tau > phi ? tau : phi;", "double t_loc = tau + phi;"),
+    ("cost_bit_forgets_delta", "double t_bit = tau + delta + psi;", "double t_bit = tau + psi;"),
+    ("cost_cd_is_min", "double t_cd = tau > phi_cd ? tau : phi_cd;", "double t_cd = tau < phi_cd ? tau : phi_cd;"),
     ("local_uses_wrong_worker", "oracle_update(w_global, w_local, grad[self],", "oracle_update(w_global, w_local, grad[num_workers - 1 - self],"),
 ]
 

@@ -537,3 +537,67 @@ def test_warmup_is_ssgd_and_hands_over_to_formal_training(oracle, warmup_n):
                                   w_before.astype(np.float64) - lr_l * grads[2].astype(np.float64))
     expect = [0] * (warmup_n + 1) + [2 if c % k == 0 else 1 for c in range(2 * k)]
     assert modes == expect
+
+
+# --------------------------------------------------------------------------
+# time-cost model (Sec. 2.1-2.3, Sec. 3.3)
+# --------------------------------------------------------------------------
+def _eq8_table(tau, phi, psi, delta, k, i):
+    """T_s^bit as the paper prints it (eq. 8)."""
+    phi_cd = delta + psi if i % k != 0 else phi
+    if tau > phi_cd:
+        return delta + psi
+    if i % k != 0:
+        return tau
+    return tau + delta + psi - phi
+
+
+def _eq9_table(tau, phi, psi, delta, k, i):
+    """T_s^loc as the paper prints it (eq. 9)."""
+    phi_cd = delta + psi if i % k != 0 else phi
+    if tau > phi:
+        return 0.0
+    if tau > phi_cd:
+        return phi - tau
+    if i % k != 0:
+        return phi - delta - psi
+    return 0.0
+
+
+def test_cost_model_against_the_printed_case_tables(oracle):
+    """The oracle computes iteration times from eq. 2, 4, 5, 6, 7 and the savings as
+    differences; the paper prints the savings as case tables (eq. 8, eq. 9).  On dyadic
+    inputs both must agree exactly (eq. 9 under its tacit assumption delta + psi <= phi)."""
+    rng = np.random.default_rng(40)
+    checked9 = 0
+    seen8, seen9 = set(), set()
+    for _ in range(4000):
+        tau, phi, psi, delta = (float(x) / 8 for x in rng.integers(0, 80, 4))
+        k = int(rng.integers(1, 7))
+        i = int(rng.integers(0, 20))
+        m = oracle.cost_model(tau, phi, psi, delta, k, i)
+        assert m["t_ssgd"] == tau + phi                       # eq. 2
+        assert m["t_bit"] == tau + delta + psi                # eq. 5
+        assert m["t_loc"] == max(tau, phi)                    # eq. 4
+        assert m["phi_cd"] == (phi if i % k == 0 else delta + psi)   # eq. 6
+        assert m["t_cd"] == max(tau, m["phi_cd"])             # eq. 7
+        assert m["save_vs_bit"] == _eq8_table(tau, phi, psi, delta, k, i)
+        seen8.add((tau > m["phi_cd"], i % k != 0))
+        if delta + psi <= phi:
+            assert m["save_vs_loc"] == _eq9_table(tau, phi, psi, delta, k, i)
+            checked9 += 1
+            seen9.add((tau > phi, tau > m["phi_cd"], i % k != 0))
+    assert checked9 > 500 and len(seen8) == 4 and len(seen9) >= 5
+
+
+def test_cost_model_average_when_communication_dominates(oracle):
+    """Sec. 3.3: with tau below every communication time the mean CD-SGD iteration over a
+    period of k is ((k-1)(delta+psi)+phi)/k; CD-SGD always beats the local-update mechanism
+    there, and beats BIT-SGD on every compressed iteration."""
+    tau, phi, psi, delta = 1.0, 16.0, 2.0, 0.5
+    for k in (1, 2, 5, 20):
+        ts = [oracle.cost_model(tau, phi, psi, delta, k, i) for i in range(k)]
+        mean_cd = sum(t["t_cd"] for t in ts) / k
+        assert mean_cd == ((k - 1) * (delta + psi) + phi) / k
+        assert all(t["save_vs_loc"] >= 0 for t in ts)
+        assert all(t["save_vs_bit"] > 0 for i, t in enumerate(ts) if i % k != 0)
