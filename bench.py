@@ -63,11 +63,24 @@ def time_workload(name, steps, warmup, want_correction=True, want_unfused=False)
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / len(step_numbers)   # ms per step
 
+    def per_step(step_numbers, fn):
+        """One event pair per step: the median is robust against a stray slow step."""
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(step_numbers) + 1)]
+        ev[0].record(stream)
+        for i, s in enumerate(step_numbers):
+            fn(s)
+            ev[i + 1].record(stream)
+        torch.cuda.synchronize()
+        d = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(len(step_numbers)))
+        return d[len(d) // 2], d[0]
+
     run(_compressed_steps(cfg.k, max(warmup, 1)), wl.fused_step)
     ms = run(_compressed_steps(cfg.k, steps), wl.fused_step)
+    med, best = per_step(_compressed_steps(cfg.k, max(10, min(steps, 40))), wl.fused_step)
     out = dict(workload=name, tensors=cfg.num_tensors, elements=cfg.elements, num_workers=cfg.num_workers,
                k=cfg.k, threshold=cfg.threshold, bytes_per_element=cfg.bytes_per_element,
-               ms_per_step=ms,
+               ms_per_step=ms, median_ms_per_step=med, min_ms_per_step=best,
                elems_per_s=cfg.elements / (ms * 1e-3),
                gbs=cfg.elements * cfg.bytes_per_element / (ms * 1e-3) / 1e9)
     out["frac_hbm_peak"] = out["gbs"] / HBM_PEAK_GBS
@@ -86,6 +99,48 @@ def time_workload(name, steps, warmup, want_correction=True, want_unfused=False)
         run([1], qp)
         out["quantize_pack_ms"] = run([1] * max(3, steps // 4), qp)
     return out, wl
+
+
+def time_small(name, steps=200):
+    """Launch-bound workloads (everything fits in cache): microseconds per fused step, called
+    eagerly and replayed from a HIP graph that holds one period of k steps."""
+    import torch
+    from paper_2106_10796_amd import runner, synth
+    cfg = synth.config(name)
+    wl = runner.Workload(cfg)
+    wl.prepare_step(0)
+    wl.prepare_step(1)
+    period = list(range(cfg.k))
+    reps = max(1, steps // cfg.k)
+
+    def run_period():
+        for s in period:
+            wl.fused_step(s)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / (reps * cfg.k) * 1e6
+
+    eager_us = timed(run_period)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run_period()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run_period()
+    graph_us = timed(graph.replay)
+    wl.destroy()
+    return {"workload": name, "tensors": cfg.num_tensors, "elements": cfg.elements,
+            "us_per_step_eager": eager_us, "us_per_step_hip_graph": graph_us,
+            "note": "one period of k steps (1 correction + k-1 compressed) per graph; wall clock incl. launch"}
 
 
 def time_correction_sum(name, steps, warmup):
@@ -222,13 +277,14 @@ def cpu_baseline(wl, target_seconds=12.0):
         Wl = np.empty(hi - lo, np.float32)
         O.update(W[lo:hi], Wl, g[lo:hi], agg, cfg.lr, cfg.lr, N)
 
-    def timed(n):
-        n = max(16 * cores, n // (16 * cores) * (16 * cores))
+    def timed(n, threads=None):
+        threads = threads or cores
+        n = max(16 * threads, n // (16 * threads) * (16 * threads))
         g, r, W, peers = sample(n)
-        per = n // cores
+        per = n // threads
         t0 = time.perf_counter()
-        with cf.ThreadPoolExecutor(cores) as ex:
-            futs = [ex.submit(work, g, r, W, peers, c * per, (c + 1) * per) for c in range(cores)]
+        with cf.ThreadPoolExecutor(threads) as ex:
+            futs = [ex.submit(work, g, r, W, peers, c * per, (c + 1) * per) for c in range(threads)]
             for f in futs:
                 f.result()
         return n, time.perf_counter() - t0
@@ -244,8 +300,11 @@ def cpu_baseline(wl, target_seconds=12.0):
         dt1 += dt
     dt1 /= reps
     gbs = n1 * cfg.bytes_per_element / dt1 / 1e9
+    n_one, dt_one = timed(max(1 << 20, n1 // cores), threads=1)      # the same loop on one core
     return {"value": gbs, "unit": "GB/s", "cores": cores, "kind": "oracle",
             "elems_per_s": n1 / dt1,
+            "one_core": {"value": n_one * cfg.bytes_per_element / dt_one / 1e9, "unit": "GB/s",
+                         "elems_per_s": n_one / dt_one, "sample_elements": n_one},
             "sample": "first %d elements of tensor %d of %s, one compressed step of worker 0 "
                       "(quantise+pack, decode-sum of %d streams, both updates), mean of %d passes of %.2f s wall"
                       % (n1, big, cfg.name, N, reps, dt1)}
@@ -297,6 +356,8 @@ def main():
         torch.cuda.empty_cache()
         extra["overlap_demo"] = overlap_demo(args.workload)
         torch.cuda.empty_cache()
+        for name in ("c1_single", "c2_resnet20"):
+            extra[name] = time_small(name)
         # the paper's time model (Sec. 3.3) fed with the measured delta; tau and the wire are assumptions
         n_el, k = head["elements"], head["k"]
         wire = 56e9 / 8                                   # the paper's 56 Gbps InfiniBand, bytes/s

@@ -126,3 +126,45 @@ def test_split_step_equals_fused(P, oracle, t_pow2):
             assert torch.equal(x.view(torch.int32), y.view(torch.int32)), "%s differs at step %d" % (key, s)
     a.destroy()
     b.destroy()
+
+
+def test_fused_steps_in_a_hip_graph_replay_like_eager(P):
+    """The step is launch-bound on small layer lists, so a caller may capture a run of steps
+    in a HIP graph.  The library enqueues kernels only (no memset or copy nodes), so a captured
+    period of k steps must replay, several times and with eager work in between, to exactly
+    the state the eager calls reach."""
+    pkg, runner, synth = P
+    cfg = synth.config("c2_resnet20")
+    a = runner.Workload(cfg, dense=True)     # eager
+    b = runner.Workload(cfg, dense=True)     # graph
+    for wl in (a, b):
+        wl.prepare_step(0)                   # agg_full for the correction step of the period
+        wl.prepare_step(1)                   # own gradient and the peers' packed streams
+    period = list(range(cfg.k))              # one correction step + k-1 compressed steps
+
+    def run_period(wl):
+        for s in period:
+            wl.fused_step(s)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):            # warm-up on the capture stream, as torch asks
+        run_period(b)
+    torch.cuda.current_stream().wait_stream(side)
+    run_period(a)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run_period(b)
+    for rep in range(4):
+        graph.replay()
+        run_period(a)
+        torch.cuda.synchronize()
+        # eager work between the replays, touching other memory
+        junk = torch.randn(1 << 20, device="cuda").sum().item()
+        assert junk == junk
+        for key in ("w_global", "w_local", "residual", "packed_self"):
+            x, y = getattr(a, key), getattr(b, key)
+            assert torch.equal(x.view(torch.int32), y.view(torch.int32)), "%s differs after replay %d" % (key, rep)
+    a.destroy()
+    b.destroy()
