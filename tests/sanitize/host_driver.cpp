@@ -1,0 +1,54 @@
+// Drives the host-only parts of the library for a build with AddressSanitizer and
+// UBSan: the time-cost model, and every argument check of the C ABI that returns before
+// any HIP call (fake, well aligned, never dereferenced device addresses).
+#include <cmath>
+#include <cstdint>
+#include <cstdio>
+#include <vector>
+
+#include "cdsgd.h"
+#include "cdsgd_cost_model.h"
+
+int main()
+{
+    int bad = 0;
+    float *A = reinterpret_cast<float *>(0x1000);
+    uint32_t *P = reinterpret_cast<uint32_t *>(0x2000);
+    bad += cdsgd_quantize_pack(nullptr, A, P, 16, 0.5f, nullptr) != CDSGD_ERR_NULL;
+    bad += cdsgd_quantize_pack(A, A, P, 0, 0.5f, nullptr) != CDSGD_ERR_SIZE;
+    bad += cdsgd_quantize_pack(A, A, P, 16, -1.0f, nullptr) != CDSGD_ERR_PARAM;
+    bad += cdsgd_quantize_pack(A + 1, A, P, 16, 0.5f, nullptr) != CDSGD_ERR_ALIGN;
+    const uint32_t *two[2] = {P, nullptr};
+    bad += cdsgd_decode_sum(two, 2, A, 16, 0.5f, nullptr) != CDSGD_ERR_NULL;
+    bad += cdsgd_decode_sum(two, 65, A, 16, 0.5f, nullptr) != CDSGD_ERR_WORKERS;
+    bad += cdsgd_update(A, A, nullptr, A, 16, 0.1f, 0.1f, 2, nullptr) != CDSGD_ERR_NULL;
+    bad += cdsgd_update(A, A, A, A, 16, NAN, 0.1f, 2, nullptr) != CDSGD_ERR_PARAM;
+    cdsgd_tensor t = {A, A, A, A, P, A, 0};
+    cdsgd_plan *plan = nullptr;
+    const uint32_t *row[1] = {P};
+    const uint32_t *const *rows[2] = {nullptr, row};
+    bad += cdsgd_plan_create(&t, 1, rows, 2, 0, &plan) != CDSGD_ERR_SIZE;   // n == 0
+    t.n = (size_t)1 << 50;                                                   // too many chunks for one launch
+    bad += cdsgd_plan_create(&t, 1, rows, 2, 0, &plan) != CDSGD_ERR_SIZE;
+    t.n = 100;
+    bad += cdsgd_plan_create(&t, 1, rows, 2, 5, &plan) != CDSGD_ERR_WORKERS;
+    bad += cdsgd_plan_create(&t, 1, nullptr, 2, 0, &plan) != CDSGD_ERR_NULL;
+    bad += cdsgd_step_fused(nullptr, 0, 1, 0.5f, 0.1f, 0.1f, nullptr) != CDSGD_ERR_NULL;
+    bad += cdsgd_step_warmup(nullptr, 0, 0, 0.1f, 0.1f, nullptr) != CDSGD_ERR_NULL;
+    bad += cdsgd_packed_words(17) != 2;
+    cdsgd_trainer *tr = nullptr;
+    bad += cdsgd_trainer_create(reinterpret_cast<cdsgd_plan *>(A), 2, 4, 0.5f, 0.1f, 0.1f, &tr) != CDSGD_OK;
+    bad += cdsgd_trainer_iteration(tr) != 0;
+    bad += cdsgd_trainer_destroy(tr) != CDSGD_OK;
+    cdsgd_cost_params p = {1.0, 5.0, 1.0, 0.5, 4};
+    cdsgd_cost c;
+    double sum = 0;
+    for (long i = 0; i < 16; ++i) {
+        bad += cdsgd_cost_iteration(&p, i, &c) != 0;
+        sum += c.t_cd + c.save_vs_bit + c.save_vs_loc;
+    }
+    bad += cdsgd_cost_period_mean(&p, &c) != 0;
+    bad += std::fabs(c.t_cd - 2.375) > 1e-12;
+    std::printf("host driver: %d failed checks, sum %.3f\n", bad, sum);
+    return bad ? 1 : 0;
+}
