@@ -261,13 +261,20 @@ def cpu_baseline(wl, target_seconds=12.0):
     avail = cfg.sizes[big] // 16 * 16
 
     def sample(n):
+        """Inputs of the sample, none of them produced by the HIP path: the own gradient and the
+        weights are the synthetic buffers; each peer's packed words are made here by the oracle from
+        a rotated copy of the same gradient values (same distribution, different alignment)."""
         sl = slice(0, n)
-        wsl = slice(0, n // 16)
         g = wl.view(wl.grad, big)[sl].cpu().numpy()
         r = np.zeros(n, np.float32)
         W = wl.view(wl.w_global, big)[sl].cpu().numpy()
-        peers = [None if j == wl.self_rank else
-                 wl.pview(wl.peer_packed[j], big)[wsl].cpu().numpy().view(np.uint32) for j in range(N)]
+        peers = []
+        for j in range(N):
+            if j == wl.self_rank:
+                peers.append(None)
+                continue
+            gj = np.ascontiguousarray(np.roll(g, 4099 * (j + 1)))
+            peers.append(O.quantize_pack(gj, np.zeros(n, np.float32), t))
         return g, r, W, peers
 
     def work(g, r, W, peers, lo, hi):
@@ -277,30 +284,34 @@ def cpu_baseline(wl, target_seconds=12.0):
         Wl = np.empty(hi - lo, np.float32)
         O.update(W[lo:hi], Wl, g[lo:hi], agg, cfg.lr, cfg.lr, N)
 
+    n_max = min(avail, 1 << 24)
+    G, R0, W0, PEERS = sample(n_max)
+
     def timed(n, threads=None):
         threads = threads or cores
-        n = max(16 * threads, n // (16 * threads) * (16 * threads))
-        g, r, W, peers = sample(n)
+        n = max(16 * threads, min(n, n_max) // (16 * threads) * (16 * threads))
+        r = R0[:n].copy()          # each pass starts from a zero residual
+        W = W0[:n].copy()
         per = n // threads
         t0 = time.perf_counter()
         with cf.ThreadPoolExecutor(threads) as ex:
-            futs = [ex.submit(work, g, r, W, peers, c * per, (c + 1) * per) for c in range(threads)]
+            futs = [ex.submit(work, G, r, W, PEERS, c * per, (c + 1) * per) for c in range(threads)]
             for f in futs:
                 f.result()
         return n, time.perf_counter() - t0
 
-    # size the sample for about `target_seconds` of CPU work in total (all cores together)
-    n0, dt0 = timed(min(avail, 1 << 20))
+    # about `target_seconds` of CPU work in total (all cores together), as repeated passes over the sample
+    n0, dt0 = timed(1 << 20)
     rate = n0 / max(dt0, 1e-6)                                  # elements per second, all cores
-    n1 = int(min(avail, max(n0, rate * target_seconds / cores * 0.5)))
+    n1 = n_max
     reps = max(1, int(round(rate * target_seconds / cores / n1)))
     dt1 = 0.0
-    for _ in range(reps):                                       # each pass starts from a zero residual
+    for _ in range(reps):
         n1, dt = timed(n1)
         dt1 += dt
     dt1 /= reps
     gbs = n1 * cfg.bytes_per_element / dt1 / 1e9
-    n_one, dt_one = timed(max(1 << 20, n1 // cores), threads=1)      # the same loop on one core
+    n_one, dt_one = timed(max(1 << 20, n1 // 4), threads=1)          # the same loop on one core
     return {"value": gbs, "unit": "GB/s", "cores": cores, "kind": "oracle",
             "elems_per_s": n1 / dt1,
             "one_core": {"value": n_one * cfg.bytes_per_element / dt_one / 1e9, "unit": "GB/s",

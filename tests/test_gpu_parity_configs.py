@@ -175,7 +175,8 @@ def test_c3_resnet50_full_size_sampled(P, oracle, dense):
     cfg = P[2].config("c3_resnet50")
     rng = np.random.default_rng(33)
     blocks = _sample_blocks(cfg, rng, 24, 1 << 13)
-    nz, tot = _run(P, oracle, cfg, dense, 10, blocks, shadow=True)
+    # the literal recipe runs all 50 iterations (7 correction / 43 compressed), the dense one 20
+    nz, tot = _run(P, oracle, cfg, dense, cfg.iterations if not dense else 20, blocks, shadow=True)
     if dense:
         assert nz > 0.2 * tot
 
@@ -185,7 +186,8 @@ def test_c4_vgg16_full_size_sampled(P, oracle, dense):
     cfg = P[2].config("c4_vgg16")
     rng = np.random.default_rng(44)
     blocks = _sample_blocks(cfg, rng, 20, 1 << 13)
-    nz, tot = _run(P, oracle, cfg, dense, 4 if not dense else 3, blocks, shadow=True)
+    # the literal recipe runs all 20 iterations (3 correction / 17 compressed), the dense one 10
+    nz, tot = _run(P, oracle, cfg, dense, cfg.iterations if not dense else 10, blocks, shadow=True)
     if dense:
         assert nz > 0.2 * tot
 
@@ -197,8 +199,9 @@ def test_c5_flat_bucket_full_size_sampled(P, oracle):
     n = cfg.sizes[0]
     blocks = [(0, 0, 1 << 14), (0, n - (1 << 14), 1 << 14), (0, (1 << 29) - 4096, 8192),   # around 2 GiB
               (0, (1 << 28) * 3 - 4096, 8192)]
-    for _ in range(12):
-        blocks.append((0, int(rng.integers(0, n // 16 - 1024)) * 16, 1 << 13))
-    nz, tot = _run(P, oracle, cfg, False, 3, blocks, shadow=True)
+    for _ in range(28):
+        blocks.append((0, int(rng.integers(0, n // 16 - 1024)) * 16, 1 << 14))
+    # all 10 iterations: one correction, nine compressed
+    nz, tot = _run(P, oracle, cfg, False, cfg.iterations, blocks, shadow=True)
     # first compressed step fires with probability exp(-2.5); later ones a little more
     assert 0.05 * tot < nz < 0.25 * tot
