@@ -50,7 +50,9 @@ typedef enum {
     CDSGD_ERR_PARAM = 3,   /* threshold not finite or <= 0, k < 1, step < 0, rate not finite, bad warm-up index */
     CDSGD_ERR_ALIGN = 4,   /* pointer alignment (see above) */
     CDSGD_ERR_WORKERS = 5, /* num_workers < 1 or > CDSGD_MAX_WORKERS, self out of range */
-    CDSGD_ERR_DEVICE = 6   /* a HIP call failed (allocation, copy, launch) */
+    CDSGD_ERR_DEVICE = 6,  /* a HIP call failed (allocation, copy, launch) */
+    CDSGD_ERR_ALIAS = 7    /* buffers that must be distinct overlap (an output with an input or
+                              with another output of the same tensor) */
 } cdsgd_status;
 
 #define CDSGD_MAX_WORKERS 64

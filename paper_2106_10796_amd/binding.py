@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_PKG, "libcdsgd.so")
 
 MAX_WORKERS = 64
 PASS_WARMUP, PASS_COMPRESSED, PASS_CORRECTION = 0, 1, 2
-OK, ERR_NULL, ERR_SIZE, ERR_PARAM, ERR_ALIGN, ERR_WORKERS, ERR_DEVICE = range(7)
+OK, ERR_NULL, ERR_SIZE, ERR_PARAM, ERR_ALIGN, ERR_WORKERS, ERR_DEVICE, ERR_ALIAS = range(8)
 
 
 class CdsgdError(RuntimeError):

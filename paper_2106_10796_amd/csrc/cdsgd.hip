@@ -647,6 +647,14 @@ __global__ __launch_bounds__(CDSGD_BLOCK) void k_fused_full(const TensorDesc *__
 // ---------------------------------------------------------------------------
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
+// Do the byte ranges [a, a + bytes) and [b, b + bytes) share a byte?  (NULL never overlaps.)
+inline bool overlap(const void *a, const void *b, size_t bytes)
+{
+    if (!a || !b) return false;
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    return x < y ? y - x < bytes : x - y < bytes;
+}
+
 inline unsigned long long packed_bytes_of(size_t n) { return 4ull * ((n + 15) / 16); }
 
 // Chunks needed to cover a tensor's packed stream (which covers its elements):
@@ -747,6 +755,7 @@ const char *cdsgd_status_string(int status)
     case CDSGD_ERR_ALIGN: return "pointer not aligned (fp32 buffers 16 bytes, packed buffers 4 bytes)";
     case CDSGD_ERR_WORKERS: return "bad worker count or worker index";
     case CDSGD_ERR_DEVICE: return "a HIP call failed";
+    case CDSGD_ERR_ALIAS: return "buffers that must be distinct overlap";
     default: return "unknown status";
     }
 }
@@ -758,6 +767,7 @@ int cdsgd_quantize_pack(const float *grad, float *residual, uint32_t *packed, si
     if (n == 0 || chunks_of(n) > kMaxGrid) return CDSGD_ERR_SIZE;
     if (!good_threshold(threshold)) return CDSGD_ERR_PARAM;
     if (!aligned(grad, 16) || !aligned(residual, 16) || !aligned(packed, 4)) return CDSGD_ERR_ALIGN;
+    if (overlap(grad, residual, n * sizeof(float))) return CDSGD_ERR_ALIAS;
     const unsigned grid = (unsigned)chunks_of(n);
     hipLaunchKernelGGL(k_quantize_pack, dim3(grid), dim3(kBlock), 0, (hipStream_t)hip_stream, grad, residual,
                        reinterpret_cast<uint8_t *>(packed), extent_of(n), threshold);
@@ -803,6 +813,10 @@ int cdsgd_update(float *w_global, float *w_local, const float *grad_local, const
     if (num_workers < 1 || num_workers > CDSGD_MAX_WORKERS) return CDSGD_ERR_WORKERS;
     if (!aligned(w_global, 16) || !aligned(w_local, 16) || !aligned(grad_local, 16) || !aligned(agg, 16))
         return CDSGD_ERR_ALIGN;
+    if (overlap(w_global, w_local, n * sizeof(float)) || overlap(w_local, grad_local, n * sizeof(float)) ||
+        overlap(w_local, agg, n * sizeof(float)) || overlap(w_global, grad_local, n * sizeof(float)) ||
+        overlap(w_global, agg, n * sizeof(float)))
+        return CDSGD_ERR_ALIAS;
     const unsigned grid = (unsigned)chunks_of(n);
     const float scale = lr_global / (float)num_workers;
     hipStream_t s = (hipStream_t)hip_stream;
@@ -835,6 +849,12 @@ int cdsgd_plan_create(const cdsgd_tensor *tensors, int num_tensors, const uint32
         if (!aligned(t.w_global, 16) || !aligned(t.w_local, 16) || !aligned(t.residual, 16) ||
             !aligned(t.grad, 16) || !aligned(t.agg_full, 16) || !aligned(t.packed_self, 4))
             return CDSGD_ERR_ALIGN;
+        const size_t fb = t.n * sizeof(float);
+        if (overlap(t.w_global, t.w_local, fb) || overlap(t.residual, t.grad, fb) ||
+            overlap(t.w_global, t.grad, fb) || overlap(t.w_global, t.residual, fb) ||
+            overlap(t.w_local, t.grad, fb) || overlap(t.w_local, t.residual, fb) ||
+            overlap(t.agg_full, t.w_global, fb) || overlap(t.agg_full, t.w_local, fb))
+            return CDSGD_ERR_ALIAS;
         all_agg = all_agg && t.agg_full != nullptr;
         total_chunks += chunks_of(t.n);
         if (total_chunks > kMaxGrid) return CDSGD_ERR_SIZE;

@@ -47,7 +47,7 @@ def test_packed_words(L):
 
 def test_status_strings(L):
     seen = set()
-    for s in range(7):
+    for s in range(8):
         msg = L.cdsgd_status_string(s)
         assert msg and msg not in seen
         seen.add(msg)
@@ -107,7 +107,8 @@ def test_update_argument_errors(L):
 def _tensor(L, **kw):
     from paper_2106_10796_amd.binding import cdsgd_tensor
     t = cdsgd_tensor()
-    t.w_global = t.w_local = t.residual = t.grad = t.packed_self = t.agg_full = A
+    # distinct fake addresses 64 KiB apart: the buffers of a tensor must not overlap
+    t.w_global, t.w_local, t.residual, t.grad, t.packed_self, t.agg_full = (A + 0x10000 * i for i in range(6))
     t.n = 64
     for k, v in kw.items():
         setattr(t, k, v)
@@ -149,6 +150,32 @@ def test_plan_and_step_argument_errors(L):
     assert step(fake, -1, 4, 0.5, 0.1, 0.1, None) == ERR_PARAM
     assert step(fake, 1, 4, 0.0, 0.1, 0.1, None) == ERR_PARAM
     assert step(fake, 1, 4, 0.5, float("nan"), 0.1, None) == ERR_PARAM
+
+
+def test_aliasing_is_refused(L):
+    """An output that overlaps an input (or another output) of the same tensor would make the
+    result depend on the launch order; the host checks refuse it."""
+    from paper_2106_10796_amd.binding import ERR_ALIAS, cdsgd_tensor
+    B1, B2, B3, B4, B5, B6 = (0x100000 * i for i in range(1, 7))
+    n = 1000
+    assert L.cdsgd_quantize_pack(B1, B1, B3, n, 0.5, None) == ERR_ALIAS
+    assert L.cdsgd_quantize_pack(B1, B1 + 4 * n - 16, B3, n, 0.5, None) == ERR_ALIAS      # partial overlap
+    assert L.cdsgd_update(B1, B1, B2, B3, n, 0.1, 0.1, 2, None) == ERR_ALIAS              # w_local on w_global
+    assert L.cdsgd_update(B1, B2, B2, B3, n, 0.1, 0.1, 2, None) == ERR_ALIAS              # w_local on grad
+    assert L.cdsgd_update(B1, B2, B3, B1 + 16, n, 0.1, 0.1, 2, None) == ERR_ALIAS         # agg on w_global
+    out = ctypes.c_void_p()
+    row = (ctypes.c_void_p * 1)(B6)
+    rows = (ctypes.POINTER(ctypes.c_void_p) * 2)(ctypes.POINTER(ctypes.c_void_p)(),
+                                                 ctypes.cast(row, ctypes.POINTER(ctypes.c_void_p)))
+    def tensor(**kw):
+        t = cdsgd_tensor()
+        t.w_global, t.w_local, t.residual, t.grad, t.packed_self, t.agg_full, t.n = B1, B2, B3, B4, B5, None, n
+        for k, v in kw.items():
+            setattr(t, k, v)
+        return (cdsgd_tensor * 1)(t)
+    for bad in (dict(w_local=B1), dict(residual=B4), dict(grad=B1 + 64), dict(w_local=B3), dict(agg_full=B2)):
+        assert L.cdsgd_plan_create(tensor(**bad), 1, rows, 2, 0, ctypes.byref(out)) == ERR_ALIAS
+    assert out.value is None
 
 
 def test_warmup_and_trainer_argument_errors(L):

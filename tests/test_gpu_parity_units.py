@@ -298,3 +298,10 @@ def test_tensor_beyond_2_to_32_elements(B, oracle):
     # the last packed word's unused bits are zero
     assert int(pself[-1].item()) >> (2 * (n % 16)) == 0
     plan.destroy()
+
+
+def test_fused_step_many_tiny_tensors(B, oracle):
+    """1500 tensors of 1..300 elements in one launch (a chunk table of 1500 tail chunks)."""
+    rng = np.random.default_rng(77)
+    sizes = [int(x) for x in rng.integers(1, 301, 1500)]
+    _run_layer_list(B, oracle, sizes, 4, 2, k=2, t=0.5, steps=3, seed=5100)
