@@ -39,11 +39,12 @@ def _compressed_steps(k, count, start=1):
     return out
 
 
-def time_workload(name, steps, warmup, want_correction=True, want_unfused=False):
+def time_workload(name, steps, warmup, want_correction=True, want_unfused=False, grad_dtype=None):
     import torch
     from paper_2106_10796_amd import runner, synth
     cfg = synth.config(name)
-    wl = runner.Workload(cfg)
+    wl = runner.Workload(cfg, grad_dtype=grad_dtype or torch.float32)
+    grad_bytes = 4 if grad_dtype in (None, torch.float32) else 2
     # inputs of a compressed step (own gradient, the peers' packed streams) and of a correction step
     if want_correction:
         wl.prepare_step(0)
@@ -78,17 +79,18 @@ def time_workload(name, steps, warmup, want_correction=True, want_unfused=False)
     run(_compressed_steps(cfg.k, max(warmup, 1)), wl.fused_step)
     ms = run(_compressed_steps(cfg.k, steps), wl.fused_step)
     med, best = per_step(_compressed_steps(cfg.k, max(10, min(steps, 40))), wl.fused_step)
+    bpe = cfg.bytes_per_element - (4 - grad_bytes)        # 24 + N/4 with fp32 gradients, 22 + N/4 with 16-bit ones
     out = dict(workload=name, tensors=cfg.num_tensors, elements=cfg.elements, num_workers=cfg.num_workers,
-               k=cfg.k, threshold=cfg.threshold, bytes_per_element=cfg.bytes_per_element,
+               k=cfg.k, threshold=cfg.threshold, bytes_per_element=bpe,
                ms_per_step=ms, median_ms_per_step=med, min_ms_per_step=best,
                elems_per_s=cfg.elements / (ms * 1e-3),
-               gbs=cfg.elements * cfg.bytes_per_element / (ms * 1e-3) / 1e9)
+               gbs=cfg.elements * bpe / (ms * 1e-3) / 1e9)
     out["frac_hbm_peak"] = out["gbs"] / HBM_PEAK_GBS
     if want_correction:
         run([0] * max(warmup, 1), wl.fused_step)
         ms_c = run([0] * max(3, steps // 4), wl.fused_step)
         out["correction_ms_per_step"] = ms_c
-        out["correction_gbs"] = cfg.elements * 20.0 / (ms_c * 1e-3) / 1e9   # read W, g, agg; write W, Wloc
+        out["correction_gbs"] = cfg.elements * (16.0 + grad_bytes) / (ms_c * 1e-3) / 1e9   # read W, g, agg; write W, Wloc
     if want_unfused:
         run(_compressed_steps(cfg.k, 1), wl.unfused_step)
         ms_u = run(_compressed_steps(cfg.k, max(2, steps // 4)), wl.unfused_step)
@@ -245,7 +247,7 @@ def overlap_demo(name, iters=12):
     return out
 
 
-def cpu_baseline(wl, target_seconds=12.0):
+def cpu_baseline(wl, target_seconds=20.0):
     """The oracle as it stands, timed on this host: worker 0's fused-equivalent work
     (quantise + pack own gradient, decode-and-sum N streams, both updates) on a bounded
     sample of the same workload, split over the host cores by element range (the work is
@@ -369,6 +371,12 @@ def main():
         torch.cuda.empty_cache()
         for name in ("c1_single", "c2_resnet20"):
             extra[name] = time_small(name)
+        r, w = time_workload(args.workload, max(5, args.steps // 2), max(2, args.warmup // 2),
+                             want_correction=False, grad_dtype=torch.bfloat16)
+        w.destroy()
+        del w
+        torch.cuda.empty_cache()
+        extra["bf16_gradients_" + args.workload] = r
         # the paper's time model (Sec. 3.3) fed with the measured delta; tau and the wire are assumptions
         n_el, k = head["elements"], head["k"]
         wire = 56e9 / 8                                   # the paper's 56 Gbps InfiniBand, bytes/s

@@ -156,6 +156,20 @@ int cdsgd_step_fused(cdsgd_plan *plan, long step, int k, float threshold, float 
                      float lr_global, void *hip_stream);
 
 /*
+ * cdsgd_plan_create for gradients in half the bytes (beyond the paper, which trains in
+ * fp32): every pass of the plan reads cdsgd_tensor.grad, and the peers' gradients bound
+ * with cdsgd_plan_bind_full_grads, as bf16 or fp16 instead of fp32 (cast the pointers;
+ * 16-byte alignment as before).  Each value is widened exactly to fp32 on load;
+ * residual, weights, aggregate and every rule stay fp32, so the result is what the fp32
+ * path gives on the widened values.  A compressed pass then moves 22 + N/4 bytes per
+ * element.  grad_dtype is a cdsgd_grad_dtype (anything else: CDSGD_ERR_PARAM).
+ */
+typedef enum { CDSGD_GRAD_F32 = 0, CDSGD_GRAD_BF16 = 1, CDSGD_GRAD_F16 = 2 } cdsgd_grad_dtype;
+int cdsgd_plan_create_typed(const cdsgd_tensor *tensors, int num_tensors,
+                            const uint32_t *const *const *peers, int num_workers, int self,
+                            int grad_dtype, cdsgd_plan **out);
+
+/*
  * Split form of cdsgd_step_fused, for overlapping the next forward pass with the
  * rest of the step (Sec. 3.2.2: once the local weights are updated the next
  * iteration can start, whatever quantisation and communication still have to do).

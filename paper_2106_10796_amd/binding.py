@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(_PKG, "libcdsgd.so")
 
 MAX_WORKERS = 64
 PASS_WARMUP, PASS_COMPRESSED, PASS_CORRECTION = 0, 1, 2
+GRAD_DTYPES = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}   # cdsgd_grad_dtype
 OK, ERR_NULL, ERR_SIZE, ERR_PARAM, ERR_ALIGN, ERR_WORKERS, ERR_DEVICE, ERR_ALIAS = range(8)
 
 
@@ -75,6 +76,9 @@ def lib():
         L.cdsgd_plan_destroy.argtypes = [vp]
         L.cdsgd_step_fused.restype = i
         L.cdsgd_step_fused.argtypes = [vp, ctypes.c_long, i, f, f, f, vp]
+        L.cdsgd_plan_create_typed.restype = i
+        L.cdsgd_plan_create_typed.argtypes = [ctypes.POINTER(cdsgd_tensor), i, ctypes.POINTER(ctypes.POINTER(vp)),
+                                              i, i, i, ctypes.POINTER(vp)]
         L.cdsgd_step_local.restype = i
         L.cdsgd_step_local.argtypes = [vp, f, vp]
         L.cdsgd_step_global.restype = i
@@ -183,8 +187,11 @@ class Plan:
     references to every tensor so that the borrowed pointers stay valid.
     """
 
-    def __init__(self, tensors, peers, num_workers, self_rank):
+    def __init__(self, tensors, peers, num_workers, self_rank, grad_dtype=torch.float32):
         T = len(tensors)
+        if grad_dtype not in GRAD_DTYPES:
+            raise TypeError("gradients must be float32, bfloat16 or float16")
+        self._grad_dtype = grad_dtype
         self._keep = (tensors, peers)
         arr = (cdsgd_tensor * max(T, 1))()
         for i, t in enumerate(tensors):
@@ -192,7 +199,7 @@ class Plan:
             arr[i].w_global = _dev(t["w_global"], torch.float32, None, "w_global").value
             arr[i].w_local = _dev(t["w_local"], torch.float32, n, "w_local").value
             arr[i].residual = _dev(t["residual"], torch.float32, n, "residual").value
-            arr[i].grad = _dev(t["grad"], torch.float32, n, "grad").value
+            arr[i].grad = _dev(t["grad"], grad_dtype, n, "grad").value
             arr[i].packed_self = _dev(t["packed_self"], PACKED_DTYPE, packed_words(n), "packed_self").value
             af = t.get("agg_full")
             arr[i].agg_full = _dev(af, torch.float32, n, "agg_full").value if af is not None else None
@@ -212,8 +219,12 @@ class Plan:
                 rows[j] = ctypes.cast(row, ctypes.POINTER(ctypes.c_void_p))
         self._sizes = [t["w_global"].numel() for t in tensors]
         handle = ctypes.c_void_p()
-        st = lib().cdsgd_plan_create(arr, T, rows if peers is not None else None, int(num_workers),
-                                     int(self_rank), ctypes.byref(handle))
+        if grad_dtype == torch.float32:
+            st = lib().cdsgd_plan_create(arr, T, rows if peers is not None else None, int(num_workers),
+                                         int(self_rank), ctypes.byref(handle))
+        else:
+            st = lib().cdsgd_plan_create_typed(arr, T, rows if peers is not None else None, int(num_workers),
+                                               int(self_rank), GRAD_DTYPES[grad_dtype], ctypes.byref(handle))
         _check(st, "cdsgd_plan_create")
         self._handle = handle
         self.num_workers = int(num_workers)
@@ -243,7 +254,7 @@ class Plan:
                 continue
             row = (ctypes.c_void_p * max(T, 1))()
             for i in range(T):
-                row[i] = _dev(peer_grads[j][i], torch.float32, self._sizes[i], "peer_grads[%d][%d]" % (j, i)).value
+                row[i] = _dev(peer_grads[j][i], self._grad_dtype, self._sizes[i], "peer_grads[%d][%d]" % (j, i)).value
             keep.append(row)
             rows[j] = ctypes.cast(row, ctypes.POINTER(ctypes.c_void_p))
         st = lib().cdsgd_plan_bind_full_grads(self._handle, rows)

@@ -66,6 +66,7 @@ constexpr unsigned kChunkQuads = kBlock * kQpl;   // quads (= packed bytes) per 
 constexpr unsigned kChunkElems = kChunkQuads * 4; // elements per chunk
 constexpr int kPeerBatch = CDSGD_PEER_BATCH;      // peers whose bytes are in flight together
 static_assert(kQpl == 1 || kQpl == 2 || kQpl == 4, "a lane's packed bytes must fit one register");
+static_assert(CDSGD_GRAD_F32 == 0 && CDSGD_GRAD_BF16 == 1 && CDSGD_GRAD_F16 == 2, "header and kernels agree");
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 
@@ -116,6 +117,54 @@ __device__ __forceinline__ void st4g(float *base, unsigned qi, int cnt, f4 v)
     if (cnt > 0) p[0] = v.x;
     if (cnt > 1) p[1] = v.y;
     if (cnt > 2) p[2] = v.z;
+}
+
+// Gradient element types: fp32, or bf16 / fp16 widened exactly to fp32 on load
+// (everything downstream of the load is the fp32 path).
+constexpr int kGradF32 = 0, kGradBF16 = 1, kGradF16 = 2;
+
+template <int GT>
+__device__ __forceinline__ constexpr unsigned grad_bytes()
+{
+    return GT == kGradF32 ? 4u : 2u;
+}
+
+typedef unsigned u2 __attribute__((ext_vector_type(2)));
+
+template <int GT>
+__device__ __forceinline__ float widen16(unsigned h)  // h: the 16-bit pattern in the low half
+{
+    if (GT == kGradBF16) return __builtin_bit_cast(float, h << 16);
+    return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
+}
+
+// One quad of a gradient buffer; `base` is the chunk's first element.
+template <bool G, int GT>
+__device__ __forceinline__ f4 ldgrad(const void *base, unsigned qi, int cnt)
+{
+    if (GT == kGradF32) return ld4g<G>(static_cast<const float *>(base), qi, cnt);
+    if (!G || cnt == 4) {
+        const u2 *p = static_cast<const u2 *>(base) + qi;
+#if CDSGD_NT_LOAD
+        const u2 v = __builtin_nontemporal_load(p);
+#else
+        const u2 v = *p;
+#endif
+        return f4{widen16<GT>(v.x & 0xFFFFu), widen16<GT>(v.x >> 16), widen16<GT>(v.y & 0xFFFFu),
+                  widen16<GT>(v.y >> 16)};
+    }
+    f4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+    const unsigned short *p = static_cast<const unsigned short *>(base) + 4u * qi;
+    if (cnt > 0) v.x = widen16<GT>(p[0]);
+    if (cnt > 1) v.y = widen16<GT>(p[1]);
+    if (cnt > 2) v.z = widen16<GT>(p[2]);
+    return v;
+}
+
+template <int GT>
+__device__ __forceinline__ const void *grad_at(const void *grad, size_t quad0)
+{
+    return static_cast<const char *>(grad) + quad0 * (4u * grad_bytes<GT>());
 }
 
 template <bool G>
@@ -286,7 +335,7 @@ struct TensorDesc {
     float *w_global;
     float *w_local;
     float *residual;
-    const float *grad;
+    const void *grad;  // fp32, bf16 or fp16 (the plan's gradient type)
     uint8_t *packed_self;
     const float *agg_full;
     Extent ext;
@@ -396,9 +445,9 @@ __global__ __launch_bounds__(CDSGD_BLOCK) void k_decode_sum(StreamTable tab, int
 }
 
 // a5 + a6 (eq. 10, eq. 11), both from the weight that was loaded.
-template <bool G, bool LOCAL, bool GLOBAL>
+template <bool G, bool LOCAL, bool GLOBAL, int GT = kGradF32>
 __device__ __forceinline__ void update_chunk(float *__restrict__ wg, float *__restrict__ wl,
-                                             const float *__restrict__ grad,
+                                             const void *__restrict__ grad,
                                              const float *__restrict__ agg, unsigned rem_elems,
                                              float lr_local, float scale)
 {
@@ -410,7 +459,7 @@ __device__ __forceinline__ void update_chunk(float *__restrict__ wg, float *__re
         const unsigned qi = j * kBlock + tid;
         cnt[j] = quad_count<G>(rem_elems, qi);
         w[j] = ld4g<G>(wg, qi, cnt[j]);
-        if (LOCAL) g[j] = ld4g<G>(grad, qi, cnt[j]);
+        if (LOCAL) g[j] = ldgrad<G, GT>(grad, qi, cnt[j]);
         if (GLOBAL) a[j] = ld4g<G>(agg, qi, cnt[j]);
     }
 #pragma unroll
@@ -450,14 +499,14 @@ __global__ __launch_bounds__(CDSGD_BLOCK) void k_update(float *__restrict__ wg, 
 }
 
 // Fused compressed step (a1-a6) for one chunk of one tensor.
-template <bool G, bool POW2, bool WRITE_LOCAL>
+template <bool G, bool POW2, bool WRITE_LOCAL, int GT>
 __device__ __forceinline__ void fused_chunk(const TensorDesc &d, const uint8_t *const *__restrict__ peers,
                                             int num_peers, int self, size_t quad0, unsigned rem_elems,
                                             unsigned rem_bytes, float t, float lr_local, float scale,
                                             float bias_t)
 {
     const unsigned tid = threadIdx.x;
-    const float *__restrict__ grad = d.grad + 4 * quad0;
+    const void *__restrict__ grad = grad_at<GT>(d.grad, quad0);
     float *__restrict__ resid = d.residual + 4 * quad0;
     float *__restrict__ wg = d.w_global + 4 * quad0;
     float *__restrict__ wl = d.w_local + 4 * quad0;
@@ -469,7 +518,7 @@ __device__ __forceinline__ void fused_chunk(const TensorDesc &d, const uint8_t *
     for (unsigned j = 0; j < kQpl; ++j) {
         const unsigned qi = j * kBlock + tid;
         cnt[j] = quad_count<G>(rem_elems, qi);
-        g[j] = ld4g<G>(grad, qi, cnt[j]);
+        g[j] = ldgrad<G, GT>(grad, qi, cnt[j]);
         r[j] = ld4g<G>(resid, qi, cnt[j]);
     }
 #pragma unroll
@@ -519,7 +568,7 @@ __device__ __forceinline__ void fused_chunk(const TensorDesc &d, const uint8_t *
 
 // peers: [num_tensors][num_peers] pointers, this worker's own row left out.
 // WRITE_LOCAL = false leaves eq. 11 to a separate, earlier launch (k_plan_local).
-template <bool POW2, bool WRITE_LOCAL>
+template <bool POW2, bool WRITE_LOCAL, int GT>
 __global__ __launch_bounds__(CDSGD_BLOCK) void k_fused_compressed(const TensorDesc *__restrict__ tensors,
                                                                   const ChunkRef *__restrict__ chunks,
                                                                   const uint8_t *const *__restrict__ peers,
@@ -531,14 +580,15 @@ __global__ __launch_bounds__(CDSGD_BLOCK) void k_fused_compressed(const TensorDe
     const size_t quad0 = (size_t)cr.chunk * kChunkQuads;
     const uint8_t *const *tp = peers + (size_t)cr.tensor * (size_t)num_peers;
     if (cr.chunk < d.ext.full_chunks)
-        fused_chunk<false, POW2, WRITE_LOCAL>(d, tp, num_peers, self, quad0, kChunkElems, kChunkQuads, t, lr_local,
+        fused_chunk<false, POW2, WRITE_LOCAL, GT>(d, tp, num_peers, self, quad0, kChunkElems, kChunkQuads, t, lr_local,
                                               scale, bias_t);
     else
-        fused_chunk<true, POW2, WRITE_LOCAL>(d, tp, num_peers, self, quad0, d.ext.tail_elems, d.ext.tail_bytes, t, lr_local,
+        fused_chunk<true, POW2, WRITE_LOCAL, GT>(d, tp, num_peers, self, quad0, d.ext.tail_elems, d.ext.tail_bytes, t, lr_local,
                                 scale, bias_t);
 }
 
 // eq. 11 alone over the layer list: w_local = W - lr_local * g (reads W, g; writes w_local).
+template <int GT>
 __global__ __launch_bounds__(CDSGD_BLOCK) void k_plan_local(const TensorDesc *__restrict__ tensors,
                                                             const ChunkRef *__restrict__ chunks, float lr_local)
 {
@@ -547,9 +597,11 @@ __global__ __launch_bounds__(CDSGD_BLOCK) void k_plan_local(const TensorDesc *__
     const size_t quad0 = (size_t)cr.chunk * kChunkQuads;
     float *wg = d.w_global + 4 * quad0;
     float *wl = d.w_local + 4 * quad0;
-    const float *grad = d.grad + 4 * quad0;
-    if (cr.chunk < d.ext.full_chunks) update_chunk<false, true, false>(wg, wl, grad, nullptr, kChunkElems, lr_local, 0.0f);
-    else update_chunk<true, true, false>(wg, wl, grad, nullptr, d.ext.tail_elems, lr_local, 0.0f);
+    const void *grad = grad_at<GT>(d.grad, quad0);
+    if (cr.chunk < d.ext.full_chunks)
+        update_chunk<false, true, false, GT>(wg, wl, grad, nullptr, kChunkElems, lr_local, 0.0f);
+    else
+        update_chunk<true, true, false, GT>(wg, wl, grad, nullptr, d.ext.tail_elems, lr_local, 0.0f);
 }
 
 // Passes that use the workers' 32-bit gradients (Alg. 1: WARMUP passes and the
@@ -564,15 +616,15 @@ __global__ __launch_bounds__(CDSGD_BLOCK) void k_plan_local(const TensorDesc *__
 constexpr int kLocalNone = 0, kLocalCopy = 1, kLocalRule = 2;
 constexpr int kFullBatch = CDSGD_FULL_BATCH;  // peers' gradients in flight together
 
-template <bool G, bool SUM, int LOCAL>
-__device__ __forceinline__ void full_chunk(const TensorDesc &d, const float *const *__restrict__ pg,
+template <bool G, bool SUM, int LOCAL, int GT>
+__device__ __forceinline__ void full_chunk(const TensorDesc &d, const void *const *__restrict__ pg,
                                            int num_peers, int self, size_t quad0, unsigned rem_elems,
                                            float lr_local, float scale)
 {
     const unsigned tid = threadIdx.x;
     float *__restrict__ wg = d.w_global + 4 * quad0;
     float *__restrict__ wl = d.w_local + 4 * quad0;
-    const float *__restrict__ grad = d.grad + 4 * quad0;
+    const void *__restrict__ grad = grad_at<GT>(d.grad, quad0);
     f4 w[kQpl], g[kQpl], a[kQpl];
     int cnt[kQpl];
 #pragma unroll
@@ -580,7 +632,7 @@ __device__ __forceinline__ void full_chunk(const TensorDesc &d, const float *con
         const unsigned qi = j * kBlock + tid;
         cnt[j] = quad_count<G>(rem_elems, qi);
         w[j] = ld4g<G>(wg, qi, cnt[j]);
-        if (SUM || LOCAL == kLocalRule) g[j] = ld4g<G>(grad, qi, cnt[j]);
+        if (SUM || LOCAL == kLocalRule) g[j] = ldgrad<G, GT>(grad, qi, cnt[j]);
         if (SUM) a[j] = f4{0.0f, 0.0f, 0.0f, 0.0f};
         else a[j] = ld4g<G>(d.agg_full + 4 * quad0, qi, cnt[j]);
     }
@@ -593,7 +645,7 @@ __device__ __forceinline__ void full_chunk(const TensorDesc &d, const float *con
                 for (int i = 0; i < kFullBatch; ++i)
 #pragma unroll
                     for (unsigned j = 0; j < kQpl; ++j)
-                        v[i][j] = ld4g<G>(pg[p + i] + 4 * quad0, j * kBlock + tid, cnt[j]);
+                        v[i][j] = ldgrad<G, GT>(grad_at<GT>(pg[p + i], quad0), j * kBlock + tid, cnt[j]);
 #pragma unroll
                 for (int i = 0; i < kFullBatch; ++i)
 #pragma unroll
@@ -602,7 +654,7 @@ __device__ __forceinline__ void full_chunk(const TensorDesc &d, const float *con
             for (; p < p_end; ++p) {
 #pragma unroll
                 for (unsigned j = 0; j < kQpl; ++j)
-                    a[j] = a[j] + ld4g<G>(pg[p] + 4 * quad0, j * kBlock + tid, cnt[j]);
+                    a[j] = a[j] + ldgrad<G, GT>(grad_at<GT>(pg[p], quad0), j * kBlock + tid, cnt[j]);
             }
         };
         add_range(0, self);
@@ -625,27 +677,35 @@ __device__ __forceinline__ void full_chunk(const TensorDesc &d, const float *con
 }
 
 // peer_grads: [num_tensors][num_peers] pointers (own row left out), or unused when !SUM.
-template <bool SUM, int LOCAL>
+template <bool SUM, int LOCAL, int GT>
 __global__ __launch_bounds__(CDSGD_BLOCK) void k_fused_full(const TensorDesc *__restrict__ tensors,
                                                             const ChunkRef *__restrict__ chunks,
-                                                            const float *const *__restrict__ peer_grads,
+                                                            const void *const *__restrict__ peer_grads,
                                                             int num_peers, int self, float lr_local,
                                                             float scale)
 {
     const ChunkRef cr = chunks[chunk_slot()];
     const TensorDesc d = tensors[cr.tensor];
     const size_t quad0 = (size_t)cr.chunk * kChunkQuads;
-    const float *const *pg = SUM ? peer_grads + (size_t)cr.tensor * (size_t)num_peers : nullptr;
+    const void *const *pg = SUM ? peer_grads + (size_t)cr.tensor * (size_t)num_peers : nullptr;
     if (cr.chunk < d.ext.full_chunks)
-        full_chunk<false, SUM, LOCAL>(d, pg, num_peers, self, quad0, kChunkElems, lr_local, scale);
+        full_chunk<false, SUM, LOCAL, GT>(d, pg, num_peers, self, quad0, kChunkElems, lr_local, scale);
     else
-        full_chunk<true, SUM, LOCAL>(d, pg, num_peers, self, quad0, d.ext.tail_elems, lr_local, scale);
+        full_chunk<true, SUM, LOCAL, GT>(d, pg, num_peers, self, quad0, d.ext.tail_elems, lr_local, scale);
 }
 
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Do [a, a + na) and [b, b + nb) share a byte?  (NULL never overlaps.)
+inline bool overlap2(const void *a, size_t na, const void *b, size_t nb)
+{
+    if (!a || !b) return false;
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    return x < y ? y - x < na : x - y < nb;
+}
 
 // Do the byte ranges [a, a + bytes) and [b, b + bytes) share a byte?  (NULL never overlaps.)
 inline bool overlap(const void *a, const void *b, size_t bytes)
@@ -701,7 +761,8 @@ struct cdsgd_plan {
     int self = 0;
     unsigned num_chunks = 0;
     bool has_agg_full = false;
-    const float **peer_grads = nullptr;  // second allocation, made by cdsgd_plan_bind_full_grads
+    const void **peer_grads = nullptr;  // second allocation, made by cdsgd_plan_bind_full_grads
+    int grad_type = kGradF32;           // element type of grad and of the bound peer gradients
 };
 
 struct cdsgd_trainer {
@@ -723,9 +784,15 @@ int launch_full_pass(cdsgd_plan *plan, int local_mode, float lr_local, float lr_
     hipStream_t s = (hipStream_t)hip_stream;
     const dim3 grid(plan->num_chunks), block(kBlock);
     const int np = plan->num_workers - 1;
-#define CDSGD_LAUNCH_FULL(SUM, LOCAL)                                                                          \
-    hipLaunchKernelGGL((k_fused_full<SUM, LOCAL>), grid, block, 0, s, plan->tensors, plan->chunks,               \
+#define CDSGD_LAUNCH_FULL_T(SUM, LOCAL, GT)                                                                    \
+    hipLaunchKernelGGL((k_fused_full<SUM, LOCAL, GT>), grid, block, 0, s, plan->tensors, plan->chunks,           \
                        plan->peer_grads, np, plan->self, lr_local, scale)
+#define CDSGD_LAUNCH_FULL(SUM, LOCAL)                                                                          \
+    do {                                                                                                       \
+        if (plan->grad_type == kGradBF16) CDSGD_LAUNCH_FULL_T(SUM, LOCAL, kGradBF16);                          \
+        else if (plan->grad_type == kGradF16) CDSGD_LAUNCH_FULL_T(SUM, LOCAL, kGradF16);                       \
+        else CDSGD_LAUNCH_FULL_T(SUM, LOCAL, kGradF32);                                                        \
+    } while (0)
     if (sum) {
         if (local_mode == kLocalNone) CDSGD_LAUNCH_FULL(true, kLocalNone);
         else if (local_mode == kLocalCopy) CDSGD_LAUNCH_FULL(true, kLocalCopy);
@@ -736,6 +803,7 @@ int launch_full_pass(cdsgd_plan *plan, int local_mode, float lr_local, float lr_
         else CDSGD_LAUNCH_FULL(false, kLocalRule);
     }
 #undef CDSGD_LAUNCH_FULL
+#undef CDSGD_LAUNCH_FULL_T
     return launch_status();
 }
 
@@ -833,9 +901,18 @@ int cdsgd_update(float *w_global, float *w_local, const float *grad_local, const
 int cdsgd_plan_create(const cdsgd_tensor *tensors, int num_tensors, const uint32_t *const *const *peers,
                       int num_workers, int self, cdsgd_plan **out)
 {
+    return cdsgd_plan_create_typed(tensors, num_tensors, peers, num_workers, self, CDSGD_GRAD_F32, out);
+}
+
+int cdsgd_plan_create_typed(const cdsgd_tensor *tensors, int num_tensors, const uint32_t *const *const *peers,
+                            int num_workers, int self, int grad_dtype, cdsgd_plan **out)
+{
     if (!out) return CDSGD_ERR_NULL;
     *out = nullptr;
     if (!tensors) return CDSGD_ERR_NULL;
+    if (grad_dtype != CDSGD_GRAD_F32 && grad_dtype != CDSGD_GRAD_BF16 && grad_dtype != CDSGD_GRAD_F16)
+        return CDSGD_ERR_PARAM;
+    const size_t grad_elem = grad_dtype == CDSGD_GRAD_F32 ? 4 : 2;
     if (num_tensors < 1) return CDSGD_ERR_SIZE;
     if (num_workers < 1 || num_workers > CDSGD_MAX_WORKERS || self < 0 || self >= num_workers)
         return CDSGD_ERR_WORKERS;
@@ -849,11 +926,11 @@ int cdsgd_plan_create(const cdsgd_tensor *tensors, int num_tensors, const uint32
         if (!aligned(t.w_global, 16) || !aligned(t.w_local, 16) || !aligned(t.residual, 16) ||
             !aligned(t.grad, 16) || !aligned(t.agg_full, 16) || !aligned(t.packed_self, 4))
             return CDSGD_ERR_ALIGN;
-        const size_t fb = t.n * sizeof(float);
-        if (overlap(t.w_global, t.w_local, fb) || overlap(t.residual, t.grad, fb) ||
-            overlap(t.w_global, t.grad, fb) || overlap(t.w_global, t.residual, fb) ||
-            overlap(t.w_local, t.grad, fb) || overlap(t.w_local, t.residual, fb) ||
-            overlap(t.agg_full, t.w_global, fb) || overlap(t.agg_full, t.w_local, fb))
+        const size_t fb = t.n * sizeof(float), gb = t.n * grad_elem;
+        if (overlap(t.w_global, t.w_local, fb) || overlap(t.w_global, t.residual, fb) ||
+            overlap(t.w_local, t.residual, fb) || overlap(t.agg_full, t.w_global, fb) ||
+            overlap(t.agg_full, t.w_local, fb) || overlap2(t.grad, gb, t.residual, fb) ||
+            overlap2(t.grad, gb, t.w_global, fb) || overlap2(t.grad, gb, t.w_local, fb))
             return CDSGD_ERR_ALIAS;
         all_agg = all_agg && t.agg_full != nullptr;
         total_chunks += chunks_of(t.n);
@@ -926,6 +1003,7 @@ int cdsgd_plan_create(const cdsgd_tensor *tensors, int num_tensors, const uint32
     plan->self = self;
     plan->num_chunks = (unsigned)total_chunks;
     plan->has_agg_full = all_agg;
+    plan->grad_type = grad_dtype;
     *out = plan;
     return CDSGD_OK;
 }
@@ -963,9 +1041,15 @@ int launch_formal_pass(cdsgd_plan *plan, long step, int k, float threshold, floa
     const dim3 grid(plan->num_chunks), block(kBlock);
     const int num_peers = plan->num_workers - 1;
     const float bias_t = -(2.0f * (float)plan->num_workers) * threshold;
-#define CDSGD_LAUNCH_COMPRESSED(POW2, LOCAL)                                                                  \
-    hipLaunchKernelGGL((k_fused_compressed<POW2, LOCAL>), grid, block, 0, s, plan->tensors, plan->chunks,      \
+#define CDSGD_LAUNCH_COMPRESSED_T(POW2, LOCAL, GT)                                                            \
+    hipLaunchKernelGGL((k_fused_compressed<POW2, LOCAL, GT>), grid, block, 0, s, plan->tensors, plan->chunks,  \
                        plan->peers, num_peers, plan->self, threshold, lr_local, scale, bias_t)
+#define CDSGD_LAUNCH_COMPRESSED(POW2, LOCAL)                                                                  \
+    do {                                                                                                       \
+        if (plan->grad_type == kGradBF16) CDSGD_LAUNCH_COMPRESSED_T(POW2, LOCAL, kGradBF16);                   \
+        else if (plan->grad_type == kGradF16) CDSGD_LAUNCH_COMPRESSED_T(POW2, LOCAL, kGradF16);                \
+        else CDSGD_LAUNCH_COMPRESSED_T(POW2, LOCAL, kGradF32);                                                 \
+    } while (0)
     if (is_pow2_threshold(threshold)) {
         if (with_local) CDSGD_LAUNCH_COMPRESSED(true, true);
         else CDSGD_LAUNCH_COMPRESSED(true, false);
@@ -974,6 +1058,7 @@ int launch_formal_pass(cdsgd_plan *plan, long step, int k, float threshold, floa
         else CDSGD_LAUNCH_COMPRESSED(false, false);
     }
 #undef CDSGD_LAUNCH_COMPRESSED
+#undef CDSGD_LAUNCH_COMPRESSED_T
     return launch_status();
 }
 
@@ -989,8 +1074,14 @@ int cdsgd_step_local(cdsgd_plan *plan, float lr_local, void *hip_stream)
 {
     if (!plan) return CDSGD_ERR_NULL;
     if (!std::isfinite(lr_local)) return CDSGD_ERR_PARAM;
-    hipLaunchKernelGGL(k_plan_local, dim3(plan->num_chunks), dim3(kBlock), 0, (hipStream_t)hip_stream,
-                       plan->tensors, plan->chunks, lr_local);
+    const dim3 grid(plan->num_chunks), block(kBlock);
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (plan->grad_type == kGradBF16)
+        hipLaunchKernelGGL(k_plan_local<kGradBF16>, grid, block, 0, s, plan->tensors, plan->chunks, lr_local);
+    else if (plan->grad_type == kGradF16)
+        hipLaunchKernelGGL(k_plan_local<kGradF16>, grid, block, 0, s, plan->tensors, plan->chunks, lr_local);
+    else
+        hipLaunchKernelGGL(k_plan_local<kGradF32>, grid, block, 0, s, plan->tensors, plan->chunks, lr_local);
     return launch_status();
 }
 
@@ -1005,7 +1096,7 @@ int cdsgd_plan_bind_full_grads(cdsgd_plan *plan, const float *const *const *peer
     const int np = plan->num_workers - 1;
     if (np == 0) return CDSGD_OK;  // a single worker's sum is its own gradient
     if (!peer_grads) return CDSGD_ERR_NULL;
-    std::vector<const float *> image((size_t)plan->num_tensors * (size_t)np);
+    std::vector<const void *> image((size_t)plan->num_tensors * (size_t)np);
     for (int j = 0, slot = 0; j < plan->num_workers; ++j) {
         if (j == plan->self) continue;
         if (!peer_grads[j]) return CDSGD_ERR_NULL;
@@ -1016,7 +1107,7 @@ int cdsgd_plan_bind_full_grads(cdsgd_plan *plan, const float *const *const *peer
         }
         ++slot;
     }
-    const size_t bytes = image.size() * sizeof(const float *);
+    const size_t bytes = image.size() * sizeof(const void *);
     void *dev = (void *)plan->peer_grads;
     if (!dev && hipMalloc(&dev, bytes) != hipSuccess) {
         (void)hipGetLastError();
@@ -1027,9 +1118,10 @@ int cdsgd_plan_bind_full_grads(cdsgd_plan *plan, const float *const *const *peer
         if (!plan->peer_grads) (void)hipFree(dev);
         return CDSGD_ERR_DEVICE;
     }
-    plan->peer_grads = (const float **)dev;
+    plan->peer_grads = (const void **)dev;
     return CDSGD_OK;
 }
+
 
 int cdsgd_step_warmup(cdsgd_plan *plan, long i, long warmup_steps, float lr_local, float lr_global,
                       void *hip_stream)

@@ -24,7 +24,7 @@ ALIGN_ELEMS = 1024
 
 class Workload:
     def __init__(self, cfg: synth.Config, device="cuda", dense: bool = False, self_rank: int = 0,
-                 peer_residuals: bool = True, full_grads: bool = False):
+                 peer_residuals: bool = True, full_grads: bool = False, grad_dtype=torch.float32):
         self.cfg = cfg
         self.device = torch.device(device)
         self.dense = dense
@@ -42,7 +42,9 @@ class Workload:
         self.w_global = torch.zeros(self.total, **f32)
         self.w_local = torch.zeros(self.total, **f32)
         self.residual = torch.zeros(self.total, **f32)
-        self.grad = torch.zeros(self.total, **f32)
+        # gradients may be held in bf16 / fp16 (the library widens them on load); everything else is fp32
+        self.grad_dtype = grad_dtype
+        self.grad = torch.zeros(self.total, dtype=grad_dtype, device=self.device)
         self.agg_full = torch.zeros(self.total, **f32)
         self.packed_self = torch.zeros(self.total // 16, **i32)
         self.peer_packed: List[Optional[torch.Tensor]] = [
@@ -54,14 +56,15 @@ class Workload:
         # full_grads: every peer's 32-bit gradient stays resident (what the server side would hold on a
         # correction or warm-up pass) and those passes sum in the kernel instead of reading agg_full
         self.peer_grad: List[Optional[torch.Tensor]] = [
-            None if (j == self.self_rank or not full_grads) else torch.zeros(self.total, **f32)
-            for j in range(self.N)]
+            None if (j == self.self_rank or not full_grads)
+            else torch.zeros(self.total, dtype=grad_dtype, device=self.device) for j in range(self.N)]
         self.full_grads = full_grads
         self._agg = None                                 # decoded aggregate of the unfused path
         for i in range(cfg.num_tensors):
             synth.fill_weight(self.view(self.w_global, i), cfg, i)
         self.w_local.copy_(self.w_global)
-        self.plan = binding.Plan(self._plan_tensors(), self._plan_peers(), self.N, self.self_rank)
+        self.plan = binding.Plan(self._plan_tensors(), self._plan_peers(), self.N, self.self_rank,
+                                 grad_dtype=grad_dtype)
         if full_grads and self.N > 1:
             self.plan.bind_full_grads([None if j == self.self_rank else
                                        [self.view(self.peer_grad[j], i) for i in range(cfg.num_tensors)]
@@ -116,13 +119,18 @@ class Workload:
         if not comp:
             self.agg_full.zero_()
         captured = []
+        if self._scratch is None:
+            self._scratch = torch.zeros(self.total, dtype=torch.float32, device=self.device)
+        g = self._scratch
         for j in range(self.N):
+            self._fill_arena(g, j, step)
+            if self.grad_dtype != torch.float32:
+                g.copy_(g.to(self.grad_dtype))      # round once: every worker's values are representable
             if j == self.self_rank:
-                self._fill_arena(self.grad, j, step)
-                g = self.grad
+                self.grad.copy_(g)
             else:
-                g = self.peer_grad[j] if self.full_grads else self._scratch
-                self._fill_arena(g, j, step)
+                if self.full_grads:
+                    self.peer_grad[j].copy_(g)
                 if comp:
                     if self.peer_residual[j] is None:
                         raise RuntimeError("this workload was built without peer residuals")
@@ -145,6 +153,7 @@ class Workload:
         for i in range(c.num_tensors):
             wg, wl = self.view(self.w_global, i), self.view(self.w_local, i)
             g = self.view(self.grad, i)
+            assert self.grad_dtype == torch.float32, "the three single-tensor calls take fp32 gradients"
             if self.compressed(step):
                 binding.cdsgd_quantize_pack(g, self.view(self.residual, i), self.pview(self.packed_self, i),
                                             c.threshold)

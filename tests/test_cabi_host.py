@@ -31,7 +31,8 @@ def test_header_declares_the_named_entry_points():
                  "cdsgd_plan_create", "cdsgd_plan_destroy", "cdsgd_packed_words", "cdsgd_status_string",
                  "cdsgd_plan_bind_full_grads", "cdsgd_step_warmup", "cdsgd_trainer_create",
                  "cdsgd_trainer_step", "cdsgd_trainer_iteration", "cdsgd_trainer_destroy",
-                 "cdsgd_step_local", "cdsgd_step_global", "cdsgd_cost_iteration", "cdsgd_cost_period_mean"):
+                 "cdsgd_step_local", "cdsgd_step_global", "cdsgd_cost_iteration", "cdsgd_cost_period_mean",
+                 "cdsgd_plan_create_typed"):
         assert must in names
 
 
@@ -175,6 +176,11 @@ def test_aliasing_is_refused(L):
         return (cdsgd_tensor * 1)(t)
     for bad in (dict(w_local=B1), dict(residual=B4), dict(grad=B1 + 64), dict(w_local=B3), dict(agg_full=B2)):
         assert L.cdsgd_plan_create(tensor(**bad), 1, rows, 2, 0, ctypes.byref(out)) == ERR_ALIAS
+    # a 16-bit gradient buffer is half as long: a residual right behind it is fine for bf16, not for fp32
+    tight = dict(grad=B4, residual=B4 + 2 * n + 48)       # 2n bytes of bf16, next 16-byte boundary
+    assert L.cdsgd_plan_create(tensor(**tight), 1, rows, 2, 0, ctypes.byref(out)) == ERR_ALIAS
+    assert L.cdsgd_plan_create_typed(tensor(**dict(tight, residual=B4 + 2 * n - 16)), 1, rows, 2, 0, 1,
+                                     ctypes.byref(out)) == ERR_ALIAS
     assert out.value is None
 
 
@@ -200,6 +206,8 @@ def test_warmup_and_trainer_argument_errors(L):
     assert L.cdsgd_trainer_iteration(None) == -1
     assert L.cdsgd_trainer_destroy(None) == OK
     assert L.cdsgd_plan_bind_full_grads(None, None) == ERR_NULL
+    arr = (__import__("paper_2106_10796_amd.binding", fromlist=["x"]).cdsgd_tensor * 1)(_tensor(L))
+    assert L.cdsgd_plan_create_typed(arr, 1, None, 1, 0, 7, ctypes.byref(out)) == ERR_PARAM   # unknown dtype
     assert L.cdsgd_step_local(None, 0.1, None) == ERR_NULL
     assert L.cdsgd_step_local(fake, float("nan"), None) == ERR_PARAM
     assert L.cdsgd_step_global(None, 1, 4, 0.5, 0.1, None) == ERR_NULL

@@ -168,3 +168,46 @@ def test_fused_steps_in_a_hip_graph_replay_like_eager(P):
             assert torch.equal(x.view(torch.int32), y.view(torch.int32)), "%s differs after replay %d" % (key, rep)
     a.destroy()
     b.destroy()
+
+
+@pytest.mark.parametrize("full_grads", [True, False], ids=["kernel_sum", "agg_full"])
+@pytest.mark.parametrize("dtype", ["bfloat16", "float16"])
+def test_low_precision_gradients(P, oracle, dtype, full_grads):
+    """Gradients held in bf16 / fp16 (cdsgd_plan_set_grad_dtype): every pass must give exactly
+    what the fp32 oracle gives on the widened values, through warm-up, correction and
+    compressed passes, for both thresholds' decode forms."""
+    pkg, runner, synth = P
+    gd = getattr(torch, dtype)
+    for base, N, self_rank in (("c2_resnet20", 4, 1), ("c5_flat4g", 5, 4)):
+        cfg = synth.scaled(synth.config(base), SIZES, "_lowp")
+        cfg.num_workers, cfg.k = N, 3
+        wl = runner.Workload(cfg, dense=True, self_rank=self_rank, full_grads=full_grads, grad_dtype=gd)
+        lr_l, lr_g, warmup_n = 0.4, 0.1, 1
+        trainer = pkg.Trainer(wl.plan, warmup_n, cfg.k, cfg.threshold, lr_l, lr_g)
+        blocks = [(i, 0, n) for i, n in enumerate(cfg.sizes)]
+        sims = [oracle.TrainerSimulation(wl.view(wl.w_global, i).cpu().numpy(), N, warmup_n, cfg.k, cfg.threshold,
+                                         lr_l, lr_g, self_rank) for i in range(cfg.num_tensors)]
+        fired = 0
+        for it in range(warmup_n + 1 + 2 * cfg.k):
+            count = it - warmup_n - 1
+            comp = it > warmup_n and count % cfg.k != 0
+            cap = wl.prepare_step(it, capture=blocks, compressed=comp)
+            # what the library reads is the low-precision buffer; the oracle gets its exact widening
+            own = [wl.view(wl.grad, i).float().cpu().numpy() for i in range(cfg.num_tensors)]
+            kind = trainer.step()
+            torch.cuda.synchronize()
+            for i in range(cfg.num_tensors):
+                assert np.array_equal(own[i], cap[self_rank][i])
+                mode, agg, words = sims[i].step([cap[j][i] for j in range(N)])
+                assert mode == kind
+                tag = "%s iteration %d tensor %d" % (dtype, it, i)
+                if mode == 1:
+                    assert_bits_equal(wl.pview(wl.packed_self, i).cpu().numpy(), words[self_rank].view(np.int32),
+                                      "packed " + tag)
+                    fired += int(np.count_nonzero(words[self_rank]))
+                assert_bits_equal(wl.view(wl.residual, i).cpu().numpy(), sims[i].residual[self_rank], "residual " + tag)
+                assert_bits_equal(wl.view(wl.w_global, i).cpu().numpy(), sims[i].w_global, "w_global " + tag)
+                assert_bits_equal(wl.view(wl.w_local, i).cpu().numpy(), sims[i].w_local, "w_local " + tag)
+        assert fired > 0
+        trainer.destroy()
+        wl.destroy()
