@@ -170,6 +170,18 @@ int cdsgd_plan_create_typed(const cdsgd_tensor *tensors, int num_tensors,
                             int grad_dtype, cdsgd_plan **out);
 
 /*
+ * One threshold per tensor (beyond the paper's single threshold; Sec. 2.3 observes that
+ * the parameters of a model differ too much for one value to suit them all).
+ *   thresholds  host array [num_tensors], each finite and > 0: compressed passes use
+ *               thresholds[i] for tensor i and ignore the threshold argument of the
+ *               step call (which is still validated).  NULL goes back to the call's
+ *               threshold for every tensor.
+ * Rewrites the plan's descriptor table on the device with a synchronous copy: do not
+ * call it while a pass of this plan may still be running.
+ */
+int cdsgd_plan_set_thresholds(cdsgd_plan *plan, const float *thresholds);
+
+/*
  * Split form of cdsgd_step_fused, for overlapping the next forward pass with the
  * rest of the step (Sec. 3.2.2: once the local weights are updated the next
  * iteration can start, whatever quantisation and communication still have to do).

@@ -79,6 +79,8 @@ def lib():
         L.cdsgd_plan_create_typed.restype = i
         L.cdsgd_plan_create_typed.argtypes = [ctypes.POINTER(cdsgd_tensor), i, ctypes.POINTER(ctypes.POINTER(vp)),
                                               i, i, i, ctypes.POINTER(vp)]
+        L.cdsgd_plan_set_thresholds.restype = i
+        L.cdsgd_plan_set_thresholds.argtypes = [vp, ctypes.POINTER(f)]
         L.cdsgd_step_local.restype = i
         L.cdsgd_step_local.argtypes = [vp, f, vp]
         L.cdsgd_step_global.restype = i
@@ -233,6 +235,17 @@ class Plan:
         st = lib().cdsgd_step_fused(self._handle, int(step), int(k), float(threshold), float(lr_local),
                                     float(lr_global), _stream())
         _check(st, "cdsgd_step_fused")
+
+    def set_thresholds(self, thresholds):
+        """One threshold per tensor (list of floats), or None to go back to the call's threshold."""
+        if thresholds is None:
+            st = lib().cdsgd_plan_set_thresholds(self._handle, None)
+        else:
+            if len(thresholds) != len(self._sizes):
+                raise ValueError("need one threshold per tensor")
+            arr = (ctypes.c_float * len(thresholds))(*[float(x) for x in thresholds])
+            st = lib().cdsgd_plan_set_thresholds(self._handle, arr)
+        _check(st, "cdsgd_plan_set_thresholds")
 
     def step_local(self, lr_local):
         st = lib().cdsgd_step_local(self._handle, float(lr_local), _stream())

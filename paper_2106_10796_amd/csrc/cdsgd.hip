@@ -339,6 +339,8 @@ struct TensorDesc {
     uint8_t *packed_self;
     const float *agg_full;
     Extent ext;
+    float threshold;  // > 0: this tensor's own threshold (cdsgd_plan_set_thresholds); 0: the call's
+    unsigned pad_;
 };
 
 struct ChunkRef {
@@ -572,13 +574,15 @@ template <bool POW2, bool WRITE_LOCAL, int GT>
 __global__ __launch_bounds__(CDSGD_BLOCK) void k_fused_compressed(const TensorDesc *__restrict__ tensors,
                                                                   const ChunkRef *__restrict__ chunks,
                                                                   const uint8_t *const *__restrict__ peers,
-                                                                  int num_peers, int self, float t,
-                                                                  float lr_local, float scale, float bias_t)
+                                                                  int num_peers, int self, float t_call,
+                                                                  float lr_local, float scale)
 {
     const ChunkRef cr = chunks[chunk_slot()];
     const TensorDesc d = tensors[cr.tensor];
     const size_t quad0 = (size_t)cr.chunk * kChunkQuads;
     const uint8_t *const *tp = peers + (size_t)cr.tensor * (size_t)num_peers;
+    const float t = d.threshold > 0.0f ? d.threshold : t_call;
+    const float bias_t = -(2.0f * (float)(num_peers + 1)) * t;  // exact for the count form (t = 2^e)
     if (cr.chunk < d.ext.full_chunks)
         fused_chunk<false, POW2, WRITE_LOCAL, GT>(d, tp, num_peers, self, quad0, kChunkElems, kChunkQuads, t, lr_local,
                                               scale, bias_t);
@@ -763,6 +767,9 @@ struct cdsgd_plan {
     bool has_agg_full = false;
     const void **peer_grads = nullptr;  // second allocation, made by cdsgd_plan_bind_full_grads
     int grad_type = kGradF32;           // element type of grad and of the bound peer gradients
+    std::vector<TensorDesc> host_tensors;  // host copy of the descriptor table (for cdsgd_plan_set_thresholds)
+    bool own_thresholds = false;           // every tensor carries its own threshold
+    bool own_thresholds_pow2 = false;      // ... and all of them are powers of two
 };
 
 struct cdsgd_trainer {
@@ -967,6 +974,8 @@ int cdsgd_plan_create_typed(const cdsgd_tensor *tensors, int num_tensors, const 
         ht[i].packed_self = reinterpret_cast<uint8_t *>(t.packed_self);
         ht[i].agg_full = t.agg_full;
         ht[i].ext = extent_of(t.n);
+        ht[i].threshold = 0.0f;
+        ht[i].pad_ = 0;
         const unsigned nc = (unsigned)chunks_of(t.n);
         for (unsigned c = 0; c < nc; ++c) {
             hc[ci].tensor = (unsigned)i;
@@ -1004,6 +1013,7 @@ int cdsgd_plan_create_typed(const cdsgd_tensor *tensors, int num_tensors, const 
     plan->num_chunks = (unsigned)total_chunks;
     plan->has_agg_full = all_agg;
     plan->grad_type = grad_dtype;
+    plan->host_tensors.assign(ht, ht + num_tensors);
     *out = plan;
     return CDSGD_OK;
 }
@@ -1040,17 +1050,18 @@ int launch_formal_pass(cdsgd_plan *plan, long step, int k, float threshold, floa
     hipStream_t s = (hipStream_t)hip_stream;
     const dim3 grid(plan->num_chunks), block(kBlock);
     const int num_peers = plan->num_workers - 1;
-    const float bias_t = -(2.0f * (float)plan->num_workers) * threshold;
 #define CDSGD_LAUNCH_COMPRESSED_T(POW2, LOCAL, GT)                                                            \
     hipLaunchKernelGGL((k_fused_compressed<POW2, LOCAL, GT>), grid, block, 0, s, plan->tensors, plan->chunks,  \
-                       plan->peers, num_peers, plan->self, threshold, lr_local, scale, bias_t)
+                       plan->peers, num_peers, plan->self, threshold, lr_local, scale)
 #define CDSGD_LAUNCH_COMPRESSED(POW2, LOCAL)                                                                  \
     do {                                                                                                       \
         if (plan->grad_type == kGradBF16) CDSGD_LAUNCH_COMPRESSED_T(POW2, LOCAL, kGradBF16);                   \
         else if (plan->grad_type == kGradF16) CDSGD_LAUNCH_COMPRESSED_T(POW2, LOCAL, kGradF16);                \
         else CDSGD_LAUNCH_COMPRESSED_T(POW2, LOCAL, kGradF32);                                                 \
     } while (0)
-    if (is_pow2_threshold(threshold)) {
+    // the count form of the decode needs every threshold in use to be a power of two
+    const bool pow2 = plan->own_thresholds ? plan->own_thresholds_pow2 : is_pow2_threshold(threshold);
+    if (pow2) {
         if (with_local) CDSGD_LAUNCH_COMPRESSED(true, true);
         else CDSGD_LAUNCH_COMPRESSED(true, false);
     } else {
@@ -1122,6 +1133,27 @@ int cdsgd_plan_bind_full_grads(cdsgd_plan *plan, const float *const *const *peer
     return CDSGD_OK;
 }
 
+
+int cdsgd_plan_set_thresholds(cdsgd_plan *plan, const float *thresholds)
+{
+    if (!plan) return CDSGD_ERR_NULL;
+    bool all_pow2 = true;
+    if (thresholds)
+        for (int i = 0; i < plan->num_tensors; ++i) {
+            if (!good_threshold(thresholds[i])) return CDSGD_ERR_PARAM;
+            all_pow2 = all_pow2 && is_pow2_threshold(thresholds[i]);
+        }
+    std::vector<TensorDesc> next = plan->host_tensors;
+    for (int i = 0; i < plan->num_tensors; ++i) next[(size_t)i].threshold = thresholds ? thresholds[i] : 0.0f;
+    if (hipMemcpy(plan->tensors, next.data(), sizeof(TensorDesc) * next.size(), hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipGetLastError();
+        return CDSGD_ERR_DEVICE;
+    }
+    plan->host_tensors.swap(next);
+    plan->own_thresholds = thresholds != nullptr;
+    plan->own_thresholds_pow2 = thresholds != nullptr && all_pow2;
+    return CDSGD_OK;
+}
 
 int cdsgd_step_warmup(cdsgd_plan *plan, long i, long warmup_steps, float lr_local, float lr_global,
                       void *hip_stream)

@@ -63,12 +63,18 @@ class Workload:
         for i in range(cfg.num_tensors):
             synth.fill_weight(self.view(self.w_global, i), cfg, i)
         self.w_local.copy_(self.w_global)
+        self.thresholds = None
         self.plan = binding.Plan(self._plan_tensors(), self._plan_peers(), self.N, self.self_rank,
                                  grad_dtype=grad_dtype)
         if full_grads and self.N > 1:
             self.plan.bind_full_grads([None if j == self.self_rank else
                                        [self.view(self.peer_grad[j], i) for i in range(cfg.num_tensors)]
                                        for j in range(self.N)])
+
+    def set_thresholds(self, thresholds):
+        """One threshold per tensor for the observed worker and the played peers (None: the config's)."""
+        self.thresholds = list(thresholds) if thresholds is not None else None
+        self.plan.set_thresholds(self.thresholds)
 
     # -- views ------------------------------------------------------------
     def view(self, arena: torch.Tensor, i: int) -> torch.Tensor:
@@ -134,7 +140,12 @@ class Workload:
                 if comp:
                     if self.peer_residual[j] is None:
                         raise RuntimeError("this workload was built without peer residuals")
-                    binding.cdsgd_quantize_pack(g, self.peer_residual[j], self.peer_packed[j], t)
+                    if self.thresholds is None:
+                        binding.cdsgd_quantize_pack(g, self.peer_residual[j], self.peer_packed[j], t)
+                    else:
+                        for i in range(self.cfg.num_tensors):
+                            binding.cdsgd_quantize_pack(self.view(g, i), self.view(self.peer_residual[j], i),
+                                                        self.pview(self.peer_packed[j], i), self.thresholds[i])
             if not comp:
                 self.agg_full.add_(g)   # worker order 0..N-1, fp32, from +0
             if capture is not None:

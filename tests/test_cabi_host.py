@@ -32,7 +32,7 @@ def test_header_declares_the_named_entry_points():
                  "cdsgd_plan_bind_full_grads", "cdsgd_step_warmup", "cdsgd_trainer_create",
                  "cdsgd_trainer_step", "cdsgd_trainer_iteration", "cdsgd_trainer_destroy",
                  "cdsgd_step_local", "cdsgd_step_global", "cdsgd_cost_iteration", "cdsgd_cost_period_mean",
-                 "cdsgd_plan_create_typed"):
+                 "cdsgd_plan_create_typed", "cdsgd_plan_set_thresholds"):
         assert must in names
 
 
@@ -208,6 +208,7 @@ def test_warmup_and_trainer_argument_errors(L):
     assert L.cdsgd_plan_bind_full_grads(None, None) == ERR_NULL
     arr = (__import__("paper_2106_10796_amd.binding", fromlist=["x"]).cdsgd_tensor * 1)(_tensor(L))
     assert L.cdsgd_plan_create_typed(arr, 1, None, 1, 0, 7, ctypes.byref(out)) == ERR_PARAM   # unknown dtype
+    assert L.cdsgd_plan_set_thresholds(None, None) == ERR_NULL
     assert L.cdsgd_step_local(None, 0.1, None) == ERR_NULL
     assert L.cdsgd_step_local(fake, float("nan"), None) == ERR_PARAM
     assert L.cdsgd_step_global(None, 1, 4, 0.5, 0.1, None) == ERR_NULL

@@ -211,3 +211,56 @@ def test_low_precision_gradients(P, oracle, dtype, full_grads):
         assert fired > 0
         trainer.destroy()
         wl.destroy()
+
+
+@pytest.mark.parametrize("pow2", [False, True], ids=["sigma", "pow2"])
+def test_per_tensor_thresholds(P, oracle, pow2):
+    """cdsgd_plan_set_thresholds on the literal ResNet-20 recipe (per-tensor gradient std
+    log-uniform over three decades, where a single threshold of 0.5 never fires): threshold i
+    = the tensor's std (chain form of the decode) or the nearest power of two (count form).
+    Every tensor must fire and match its own oracle run; clearing the thresholds goes back to
+    the call's threshold."""
+    import math
+    pkg, runner, synth = P
+    cfg = synth.config("c2_resnet20")
+    th = [float(np.float32(s)) for s in cfg.tensor_std]
+    if pow2:
+        th = [2.0 ** round(math.log2(s)) for s in th]
+    wl = runner.Workload(cfg, self_rank=2)
+    wl.set_thresholds(th)
+    N = cfg.num_workers
+    blocks = [(i, 0, n) for i, n in enumerate(cfg.sizes)]
+    sims = [oracle.Simulation(wl.view(wl.w_global, i).cpu().numpy(), N, cfg.k, th[i], cfg.lr, cfg.lr, 2)
+            for i in range(cfg.num_tensors)]
+    fired = np.zeros(cfg.num_tensors, np.int64)
+    for s in range(2 * cfg.k):
+        cap = wl.prepare_step(s, capture=blocks)
+        wl.fused_step(s)                      # the call's threshold (0.5) must be ignored
+        torch.cuda.synchronize()
+        for i in range(cfg.num_tensors):
+            comp, agg, words = sims[i].step([cap[j][i] for j in range(N)])
+            tag = "step %d tensor %d (t=%g)" % (s, i, th[i])
+            if comp:
+                assert_bits_equal(wl.pview(wl.packed_self, i).cpu().numpy(), words[2].view(np.int32), "packed " + tag)
+                for j in range(N):
+                    if j != 2:
+                        assert_bits_equal(wl.pview(wl.peer_packed[j], i).cpu().numpy(), words[j].view(np.int32),
+                                          "peer packed " + tag)
+                fired[i] += int(np.count_nonzero(words[2]))
+            assert_bits_equal(wl.view(wl.residual, i).cpu().numpy(), sims[i].residual[2], "residual " + tag)
+            assert_bits_equal(wl.view(wl.w_global, i).cpu().numpy(), sims[i].w_global, "w_global " + tag)
+            assert_bits_equal(wl.view(wl.w_local, i).cpu().numpy(), sims[i].w_local, "w_local " + tag)
+    assert (fired > 0).all()                  # with its own threshold every tensor sends codes
+    # back to the single threshold of the call for every tensor
+    wl.set_thresholds(None)
+    wl.prepare_step(1)
+    r_before = wl.residual.clone()
+    wl.packed_self.fill_(-1)
+    wl.fused_step(1)
+    torch.cuda.synchronize()
+    for i in range(cfg.num_tensors):
+        r = wl.view(r_before, i).cpu().numpy()
+        words = oracle.quantize_pack(wl.view(wl.grad, i).cpu().numpy(), r, cfg.threshold)
+        assert_bits_equal(wl.pview(wl.packed_self, i).cpu().numpy(), words.view(np.int32), "packed after clearing, tensor %d" % i)
+        assert_bits_equal(wl.view(wl.residual, i).cpu().numpy(), r, "residual after clearing, tensor %d" % i)
+    wl.destroy()
