@@ -26,7 +26,12 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per k_fused_compressed launch from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this
 # file, scaled by the same counters' readings for a 1 GiB device copy (FETCH_SIZE x 2.0, WRITE_SIZE
 # x 1.0 on this GPU); summaries in profiles/k_fused_compressed_<workload>.md.
-MEASURED_TRAFFIC_BYTES = {"c4_vgg16": 3.8786e9, "c3_resnet50": 0.71694e9}
+MEASURED_TRAFFIC_BYTES = {"c4_vgg16": 3.8786e9, "c3_resnet50": 0.7170e9}
+
+
+def _progress(msg):
+    """Stage marker on stderr (stdout carries the one JSON line only)."""
+    print("bench: " + msg, file=sys.stderr, flush=True)
 
 
 def _compressed_steps(k, count, start=1):
@@ -43,6 +48,7 @@ def time_workload(name, steps, warmup, want_correction=True, want_unfused=False,
     import torch
     from paper_2106_10796_amd import runner, synth
     cfg = synth.config(name)
+    _progress("%s: building the workload and the peers' streams" % name)
     wl = runner.Workload(cfg, grad_dtype=grad_dtype or torch.float32)
     grad_bytes = 4 if grad_dtype in (None, torch.float32) else 2
     # inputs of a compressed step (own gradient, the peers' packed streams) and of a correction step
@@ -76,6 +82,7 @@ def time_workload(name, steps, warmup, want_correction=True, want_unfused=False,
         d = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(len(step_numbers)))
         return d[len(d) // 2], d[0]
 
+    _progress("%s: timing %d fused steps" % (name, steps))
     run(_compressed_steps(cfg.k, max(warmup, 1)), wl.fused_step)
     ms = run(_compressed_steps(cfg.k, steps), wl.fused_step)
     med, best = per_step(_compressed_steps(cfg.k, max(10, min(steps, 40))), wl.fused_step)
@@ -346,6 +353,7 @@ def main():
     from paper_2106_10796_amd import binding
     binding.lib()   # fail loudly if the HIP library is not built
 
+    _progress("start")
     if args.calib_copy:
         src = torch.randn(1 << 28, device="cuda")
         dst = torch.empty_like(src)
@@ -358,12 +366,14 @@ def main():
                              want_unfused=not args.no_extra)
     cpu = None
     if not args.no_cpu_baseline:
+        _progress("cpu baseline (oracle on the host cores)")
         cpu = cpu_baseline(wl)
     wl.destroy()
     del wl
     torch.cuda.empty_cache()
     extra = {"headline": head}
     if not args.no_extra:
+        _progress("extras: correction with kernel sum, overlap, small workloads, bf16 gradients, other workloads")
         extra["correction_with_kernel_sum_" + args.workload] = time_correction_sum(
             args.workload, max(3, args.steps // 4), max(1, args.warmup // 2))
         torch.cuda.empty_cache()
