@@ -310,10 +310,9 @@ def cpu_baseline(wl, target_seconds=20.0):
         return n, time.perf_counter() - t0
 
     # about `target_seconds` of CPU work in total (all cores together), as repeated passes over the sample
-    n0, dt0 = timed(1 << 20)
-    rate = n0 / max(dt0, 1e-6)                                  # elements per second, all cores
-    n1 = n_max
-    reps = max(1, int(round(rate * target_seconds / cores / n1)))
+    timed(1 << 20)                                              # warm the threads and the page cache
+    n1, dt_first = timed(n_max)
+    reps = max(1, int(round(target_seconds / (cores * max(dt_first, 1e-6)))))
     dt1 = 0.0
     for _ in range(reps):
         n1, dt = timed(n1)
@@ -333,8 +332,8 @@ def cpu_baseline(wl, target_seconds=20.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=40)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c4_vgg16")
     ap.add_argument("--no-extra", action="store_true", help="skip the ResNet-50 and 4 GiB workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
