@@ -18,6 +18,10 @@
  *              except that a plan keeps (borrows) the pointers it was built from.
  *   alignment  fp32 buffers must be 16-byte aligned, packed buffers 4-byte
  *              aligned (CDSGD_ERR_ALIGN otherwise).
+ *   aliasing   Within one call or one tensor of a plan, an output buffer must not
+ *              overlap an input or another output (w_local / w_global, residual /
+ *              grad, ...): CDSGD_ERR_ALIAS.  Buffers of different tensors and the
+ *              peers' streams are not cross-checked.
  *   stream     hip_stream is a hipStream_t passed as void* (NULL = the null
  *              stream).  Work is enqueued and the call returns; nothing
  *              synchronises.
@@ -121,8 +125,8 @@ typedef struct cdsgd_plan cdsgd_plan;
 /*
  * Build a plan: copies the layer list, the peers' pointers and a chunk table to
  * the device (one small allocation, one synchronous copy; only this call and
- * cdsgd_plan_bind_full_grads allocate).  The plan borrows every data pointer: the buffers must stay alive
- * and in place while the plan is used.
+ * cdsgd_plan_bind_full_grads allocate).  The plan borrows every data pointer:
+ * the buffers must stay alive and in place while the plan is used.
  *   tensors      host array [num_tensors]
  *   peers        host array [num_workers] of host arrays [num_tensors] of device
  *                pointers: peers[j][i] is worker j's packed stream for tensor i
