@@ -254,7 +254,7 @@ def overlap_demo(name, iters=12):
     return out
 
 
-def cpu_baseline(wl, target_seconds=20.0):
+def cpu_baseline(wl, target_seconds=40.0):
     """The oracle as it stands, timed on this host: worker 0's fused-equivalent work
     (quantise + pack own gradient, decode-and-sum N streams, both updates) on a bounded
     sample of the same workload, split over the host cores by element range (the work is
@@ -349,8 +349,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
-    from paper_2106_10796_amd import binding
-    binding.lib()   # fail loudly if the HIP library is not built
+    from paper_2106_10796_amd import binding, build as hip_build
+    hip_build.ensure_built()
+    binding.lib()   # the HIP library or nothing: there is no other path
 
     _progress("start")
     if args.calib_copy:

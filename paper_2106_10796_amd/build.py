@@ -45,5 +45,11 @@ def build(extra_flags=(), out=LIB, verbose=False) -> str:
     return out
 
 
+def ensure_built() -> str:
+    """Build only if no library is there (tests, the smoke check and the benchmark call this;
+    the binding itself never builds and never falls back)."""
+    return LIB if os.path.exists(LIB) else build()
+
+
 if __name__ == "__main__":
     print(build(extra_flags=sys.argv[1:], verbose=True))

@@ -20,7 +20,8 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(scope="module")
 def P():
     import paper_2106_10796_amd as pkg
-    from paper_2106_10796_amd import runner, synth
+    from paper_2106_10796_amd import build, runner, synth
+    build.ensure_built()
     pkg.binding.lib()
     assert torch.cuda.is_available()
     return pkg, runner, synth

@@ -16,7 +16,8 @@ SIZES = [4096, 4097, 1000, 64, 10, 36864, 20011, 1]
 @pytest.fixture(scope="module")
 def P():
     import paper_2106_10796_amd as pkg
-    from paper_2106_10796_amd import runner, synth
+    from paper_2106_10796_amd import build, runner, synth
+    build.ensure_built()
     pkg.binding.lib()
     assert torch.cuda.is_available()
     return pkg, runner, synth

@@ -18,7 +18,8 @@ GUARD = 64  # sentinel elements on both sides of every output buffer
 
 @pytest.fixture(scope="module")
 def B():
-    from paper_2106_10796_amd import binding
+    from paper_2106_10796_amd import binding, build
+    build.ensure_built()
     binding.lib()
     assert torch.cuda.is_available()
     return binding
