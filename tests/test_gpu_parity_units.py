@@ -306,3 +306,34 @@ def test_fused_step_many_tiny_tensors(B, oracle):
     rng = np.random.default_rng(77)
     sizes = [int(x) for x in rng.integers(1, 301, 1500)]
     _run_layer_list(B, oracle, sizes, 4, 2, k=2, t=0.5, steps=3, seed=5100)
+
+
+def test_fused_step_random_configurations(B, oracle):
+    """Seeded random layer lists, worker counts, positions, periods and thresholds (both decode
+    forms), each checked step by step against the oracle and the three-call composition.
+    CDSGD_FUZZ_CASES raises the number of cases for a longer soak."""
+    import os
+    cases = int(os.environ.get("CDSGD_FUZZ_CASES", "40"))
+    rng = np.random.default_rng(20261127)
+    for case in range(cases):
+        T = int(rng.integers(1, 9))
+        kinds = rng.integers(0, 4, T)
+        sizes = []
+        for kind in kinds:
+            if kind == 0:
+                sizes.append(int(rng.integers(1, 70)))                       # tiny, every tail shape
+            elif kind == 1:
+                sizes.append(int(rng.integers(1, 5)) * 4096 + int(rng.integers(-3, 4)))   # around chunk edges
+            elif kind == 2:
+                sizes.append(int(rng.integers(70, 20000)))
+            else:
+                sizes.append(int(rng.integers(1, 40)) * 1024)
+        N = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 31, 33]))
+        self_rank = int(rng.integers(0, N))
+        k = int(rng.integers(1, 5))
+        t = float(rng.choice([0.5, 0.25, 2.0, 0.05, 0.3, 1e-3, 0.0625, 7.0]))
+        try:
+            _run_layer_list(B, oracle, sizes, N, self_rank, k=k, t=t, steps=int(rng.integers(2, 5)),
+                            seed=9000 + case)
+        except AssertionError as e:
+            raise AssertionError("case %d: sizes=%s N=%d self=%d k=%d t=%g: %s" % (case, sizes, N, self_rank, k, t, e))
