@@ -225,8 +225,12 @@ int cdsgd_plan_bind_full_grads(cdsgd_plan *plan, const float *const *const *peer
  * CDSGD_ERR_NULL if the plan has neither).
  *   i <  warmup_steps - 1   w_local is not written
  *   i == warmup_steps - 1   w_local = the new global weights (the copy after the pull)
- *   i == warmup_steps       w_local = W - lr_local * grad from the pre-pass W (the
- *                           local buffer holds exactly that W at this point)
+ *   i == warmup_steps       w_local = W - lr_local * grad, W being the global weights before
+ *                           this pass (eq. 11).  For warmup_steps >= 1 that W is what the
+ *                           previous pass copied into w_local; for warmup_steps == 0 Alg. 1
+ *                           has no earlier pass to make the copy, and the base is still the
+ *                           global weight: w_local is write-only in every pass, its content
+ *                           before the call is never read.
  * i outside [0, warmup_steps] is CDSGD_ERR_PARAM.
  */
 int cdsgd_step_warmup(cdsgd_plan *plan, long i, long warmup_steps, float lr_local, float lr_global,
@@ -235,8 +239,10 @@ int cdsgd_step_warmup(cdsgd_plan *plan, long i, long warmup_steps, float lr_loca
 /*
  * Alg. 1 as a whole, as a counter around cdsgd_step_warmup and cdsgd_step_fused:
  * iterations 0 .. warmup_steps are WARMUP passes, iteration warmup_steps + 1 + c is
- * FormalTraining's pass with count = c.  The trainer borrows the plan (destroy the
- * trainer first) and owns nothing on the device.
+ * FormalTraining's pass with count = c.  Every formal pass, the first one included,
+ * computes w_local from the global weights as they stand before the pass (eq. 11), not
+ * from what the last warm-up pass left in w_local.  The trainer borrows the plan
+ * (destroy the trainer first) and owns nothing on the device.
  */
 typedef enum { CDSGD_PASS_WARMUP = 0, CDSGD_PASS_COMPRESSED = 1, CDSGD_PASS_CORRECTION = 2 } cdsgd_pass;
 typedef struct cdsgd_trainer cdsgd_trainer;

@@ -33,10 +33,13 @@
  *                        differences T_loc - T_cd and T_bit - T_cd that Sec. 3.3 defines
  *
  * Every function here is pinned by tests/test_oracle_pins.py (hand-unrolled
- * recurrence, closed forms, invariants, brute force on tiny inputs).  The four
+ * recurrence, closed forms, invariants, brute force on tiny inputs).  The
  * points that are readings of a silent paper (boundary case |a| == t, the code
  * values and word layout, the initial counter value, the residual on correction
- * iterations) are pinned only to this build's stated reading.
+ * iterations, and the two hand-over readings stated at oracle_warmup_step and
+ * oracle_trainer_step: what the local buffer holds when WARMUP has n == 0, and
+ * the base of the first FormalTraining local update) are pinned only to this
+ * build's stated reading; for the last two that reading is eq. 11.
  */
 #include <math.h>
 #include <stddef.h>
@@ -170,19 +173,26 @@ int oracle_step(float *w_global, float *w_local, float *const *residual, const f
  * gradients; i is the loop counter before the pass, n the number of warm-up
  * steps (the loop runs for i = 0..n).  Every pass is plain S-SGD on the global
  * weights (eq. 1): the server sums the workers' 32-bit gradients and updates.
- *   i == n     : the local weights are first updated with the own gradient,
- *                starting from the global weights of this pass (they were copied
- *                in at i == n-1, or are the initial ones when n == 0)
- *   i == n - 1 : after the pull, the new global weights are copied into the
+ *   i == n     : the local buffer, which holds the global weights W_n of this
+ *                pass, is first updated in place with the own gradient (eq. 11
+ *                with k = n: W_loc = W_n - lr_local * g_n)
+ *   i == n - 1 : after the pull, the new global weights W_n are copied into the
  *                local buffer
+ * Reading for n == 0: the algorithm has no pass n - 1 in which to make that copy,
+ * so nothing it states ever loads the local buffer.  Eq. 11 and eq. 3 fix what
+ * the buffer must hold when it is updated -- the global weights of the pass
+ * (Sec. 3.1: the local buffer loads the global weights of the last iteration
+ * as local weights) -- so for n == 0 the copy is made at the start of pass 0,
+ * from the initial global weights.  Whatever the caller left in the local
+ * buffer is never read.
  * No quantisation happens, residuals are not touched. */
 void oracle_warmup_step(float *w_global, float *w_local, const float *const *grad, float *agg, size_t n_elems,
                         int num_workers, int self, long i, long n, float lr_local, float lr_global)
 {
     oracle_full_sum(grad, num_workers, agg, n_elems);
     if (i == n) {
-        /* the local buffer holds W_n here (the copy made at i == n-1; the caller's
-         * initial contents when n == 0) and is updated in place */
+        if (n == 0) memcpy(w_local, w_global, n_elems * sizeof(float)); /* the copy no earlier pass could make */
+        /* the local buffer holds W_n here and is updated in place */
         for (size_t e = 0; e < n_elems; ++e) w_local[e] = fmaf(-lr_local, grad[self][e], w_local[e]);
     }
     oracle_update(w_global, NULL, NULL, agg, n_elems, lr_local, lr_global, num_workers);
@@ -192,7 +202,13 @@ void oracle_warmup_step(float *w_global, float *w_local, const float *const *gra
 /* Alg. 1 end to end for iteration number `iter` (0, 1, 2, ...): iterations
  * 0..n are WARMUP passes, iteration n+1+c is FormalTraining's pass with
  * count = c.  Returns 0 for a warm-up pass, 1 for a compressed pass, 2 for a
- * correction pass. */
+ * correction pass.
+ * Reading for the hand-over: every FormalTraining pass, the first included,
+ * takes the base of its local update from the global weights as they stand
+ * before the pass (eq. 11: W_loc = W_k - lr_local * g).  In later passes that
+ * is what Alg. 1's copy after the pull left in the local buffer; WARMUP's last
+ * pass has no such copy, so read as buffer contents alone the first formal
+ * pass would start from W_n - lr_local * g_n instead of W_{n+1}.  Eq. 11 decides. */
 int oracle_trainer_step(float *w_global, float *w_local, float *const *residual, const float *const *grad,
                         uint32_t *const *word, float *agg, uint8_t *code_scratch, size_t n_elems,
                         int num_workers, int self, long iter, long warmup_n, int k, float t, float lr_local,

@@ -160,7 +160,7 @@ class Simulation:
     packed streams of that pass (None on a correction pass).
     """
 
-    def __init__(self, w0, num_workers, k, t, lr_local, lr_global, self_rank=0):
+    def __init__(self, w0, num_workers, k, t, lr_local, lr_global, self_rank=0, w_local0=None):
         self.n = w0.size
         self.N = int(num_workers)
         self.k = int(k)
@@ -170,7 +170,10 @@ class Simulation:
         self.self_rank = int(self_rank)
         self.count = 0
         self.w_global = np.array(w0, dtype=np.float32, copy=True)
-        self.w_local = np.array(w0, dtype=np.float32, copy=True)
+        # the local buffer's initial content: a copy of w0 unless the caller gives its own
+        # (a sentinel, say: Alg. 1 writes the buffer before it ever reads it)
+        self.w_local = np.array(w0 if w_local0 is None else w_local0, dtype=np.float32, copy=True)
+        assert self.w_local.size == self.n
         self.residual = [np.zeros(self.n, np.float32) for _ in range(self.N)]
         self.word = [np.zeros(packed_words(self.n), np.uint32) for _ in range(self.N)]
         self.agg = np.zeros(self.n, np.float32)
@@ -195,8 +198,8 @@ class TrainerSimulation(Simulation):
     FormalTraining.  step(grads) returns (mode, agg, words) with mode 0 = warm-up,
     1 = compressed, 2 = correction."""
 
-    def __init__(self, w0, num_workers, warmup_n, k, t, lr_local, lr_global, self_rank=0):
-        super().__init__(w0, num_workers, k, t, lr_local, lr_global, self_rank)
+    def __init__(self, w0, num_workers, warmup_n, k, t, lr_local, lr_global, self_rank=0, w_local0=None):
+        super().__init__(w0, num_workers, k, t, lr_local, lr_global, self_rank, w_local0)
         self.warmup_n = int(warmup_n)
         self.iteration = 0
 

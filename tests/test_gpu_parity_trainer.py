@@ -26,7 +26,7 @@ def P():
 @pytest.mark.parametrize("full_grads", [True, False], ids=["kernel_sum", "agg_full"])
 @pytest.mark.parametrize("warmup_n,N,self_rank,k,base", [
     (0, 4, 0, 3, "c2_resnet20"), (1, 8, 5, 4, "c2_resnet20"), (3, 16, 15, 2, "c3_resnet50"),
-    (2, 1, 0, 3, "c1_single"), (2, 3, 1, 1, "c5_flat4g")])
+    (2, 1, 0, 3, "c1_single"), (2, 3, 1, 1, "c5_flat4g"), (0, 5, 3, 2, "c5_flat4g"), (0, 1, 0, 2, "c1_single")])
 def test_trainer_matches_oracle(P, oracle, full_grads, warmup_n, N, self_rank, k, base):
     pkg, runner, synth = P
     cfg = synth.scaled(synth.config(base), SIZES, "_trainer")
@@ -35,8 +35,13 @@ def test_trainer_matches_oracle(P, oracle, full_grads, warmup_n, N, self_rank, k
     lr_l, lr_g = 0.4, 0.1
     trainer = pkg.Trainer(wl.plan, warmup_n, k, cfg.threshold, lr_l, lr_g)
     blocks = [(i, 0, n) for i, n in enumerate(cfg.sizes)]
+    # the local buffer starts at a sentinel unrelated to the weights, on both sides: Alg. 1 writes it
+    # before it ever reads it (for warmup_n = 0 the base of pass 0's local update is the global weight)
+    SENTINEL = -1234.5
+    wl.w_local.fill_(SENTINEL)
     sims = [oracle.TrainerSimulation(wl.view(wl.w_global, i).cpu().numpy(), N, warmup_n, k, cfg.threshold,
-                                     lr_l, lr_g, self_rank) for i in range(cfg.num_tensors)]
+                                     lr_l, lr_g, self_rank, w_local0=np.full(cfg.sizes[i], SENTINEL, np.float32))
+            for i in range(cfg.num_tensors)]
     kinds = []
     for it in range(warmup_n + 1 + 2 * k + 1):
         count = it - warmup_n - 1
@@ -65,6 +70,7 @@ def test_trainer_matches_oracle(P, oracle, full_grads, warmup_n, N, self_rank, k
             assert_bits_equal(gl, sims[i].w_local, "w_local bits " + tag)
             if mode == 0 and it < warmup_n - 1:
                 assert torch.equal(wl.view(wl.w_local, i), wl.view(loc_before, i)), "w_local written early " + tag
+                assert bool((wl.view(wl.w_local, i) == SENTINEL).all()), "w_local written early " + tag
     expect = [0] * (warmup_n + 1) + [2 if c % k == 0 else 1 for c in range(2 * k + 1)]
     assert kinds == expect
     trainer.destroy()
@@ -174,7 +180,7 @@ def test_fused_steps_in_a_hip_graph_replay_like_eager(P):
 @pytest.mark.parametrize("full_grads", [True, False], ids=["kernel_sum", "agg_full"])
 @pytest.mark.parametrize("dtype", ["bfloat16", "float16"])
 def test_low_precision_gradients(P, oracle, dtype, full_grads):
-    """Gradients held in bf16 / fp16 (cdsgd_plan_set_grad_dtype): every pass must give exactly
+    """Gradients held in bf16 / fp16 (cdsgd_plan_create_typed): every pass must give exactly
     what the fp32 oracle gives on the widened values, through warm-up, correction and
     compressed passes, for both thresholds' decode forms."""
     pkg, runner, synth = P

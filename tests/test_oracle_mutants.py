@@ -44,9 +44,25 @@ MUTANTS = [
      "if (i == n) memcpy(w_local, w_global, n_elems * sizeof(float));"),
     ("warmup_copy_before_update", "    oracle_update(w_global, NULL, NULL, agg, n_elems, lr_local, lr_global, num_workers);\n    if (i == n - 1) memcpy",
      "    if (i == n - 1) memcpy(w_local, w_global, n_elems * sizeof(float));\n    oracle_update(w_global, NULL, NULL, agg, n_elems, lr_local, lr_global, num_workers);\n    if (0) memcpy"),
-    ("warmup_local_update_every_pass", "if (i == n) {\n        /* the local buffer", "if (i <= n) {\n        /* the local buffer"),
+    ("warmup_local_update_every_pass", "if (i == n) {\n        if (n == 0)", "if (i <= n) {\n        if (n == 0)"),
     ("warmup_local_uses_global_rate", "w_local[e] = fmaf(-lr_local, grad[self][e], w_local[e]);",
      "w_local[e] = fmaf(-lr_global, grad[self][e], w_local[e]);"),
+    # the two rejected hand-over readings: the local buffer as the caller left it (n == 0), and the
+    # first formal local update made in place on what the warm-up left in the local buffer
+    ("warmup_n0_base_is_callers_buffer",
+     "if (n == 0) memcpy(w_local, w_global, n_elems * sizeof(float)); /* the copy no earlier pass could make */", ""),
+    ("first_formal_local_update_in_place",
+     "    return oracle_step(w_global, w_local, residual, grad, word, agg, code_scratch, n_elems, num_workers, self,\n"
+     "                       iter - warmup_n - 1,",
+     "    if (iter == warmup_n + 1) {\n"
+     "        float *keep = w_local;\n"
+     "        for (size_t e = 0; e < n_elems; ++e) keep[e] = fmaf(-lr_local, grad[self][e], keep[e]);\n"
+     "        oracle_full_sum(grad, num_workers, agg, n_elems);\n"
+     "        oracle_update(w_global, NULL, NULL, agg, n_elems, lr_local, lr_global, num_workers);\n"
+     "        return 2;\n"
+     "    }\n"
+     "    return oracle_step(w_global, w_local, residual, grad, word, agg, code_scratch, n_elems, num_workers, self,\n"
+     "                       iter - warmup_n - 1,"),
     ("warmup_one_pass_short", "if (iter <= warmup_n) {", "if (iter < warmup_n) {"),
     ("formal_count_not_reset", "iter - warmup_n - 1, k, t,", "iter, k, t,"),
     ("cost_correction_case_swapped", "double phi_cd = (i % k != 0) ? delta + psi : phi;",

@@ -485,11 +485,18 @@ def test_first_step_fire_rate_matches_laplace_tail(oracle):
 # --------------------------------------------------------------------------
 # Alg. 1 end to end: WARMUP, then FormalTraining
 # --------------------------------------------------------------------------
-def test_hand_unrolled_warmup_then_formal(oracle):
-    rows = _read_golden("hand_unrolled_warmup_n1.txt")
-    _, n, N, wn, k, t, lrl, lrg, w0 = rows[0].split()
+@pytest.mark.parametrize("fixture", ["hand_unrolled_warmup_n1.txt", "hand_unrolled_warmup_n0.txt"])
+def test_hand_unrolled_warmup_then_formal(oracle, fixture):
+    """Alg. 1 through WARMUP into FormalTraining, worked by hand.  The n = 0 fixture starts the
+    local buffer at a sentinel that differs from W0: the local update of pass 0 must start from
+    the global weight (eq. 11), and the first formal local update from the pulled W_{n+1}."""
+    rows = _read_golden(fixture)
+    fields = rows[0].split()
+    _, n, N, wn, k, t, lrl, lrg, w0 = fields[:9]
+    loc0 = f32([float(fields[9])] * int(n)) if len(fields) > 9 else None
     sim = oracle.TrainerSimulation(f32([float(w0)] * int(n)), int(N), int(wn), int(k), float(t), float(lrl),
-                                   float(lrg))
+                                   float(lrg), w_local0=loc0)
+    steps = 0
     for row in rows[1:]:
         lhs, rhs = row.split("|")
         g = [float(x) for x in lhs.split()[1:]]
@@ -500,6 +507,8 @@ def test_hand_unrolled_warmup_then_formal(oracle):
         assert sim.w_global[0] == F32(float(W))
         assert sim.w_local[0] == F32(float(Wloc))
         assert sim.residual[0][0] == F32(float(r0)) and sim.residual[1][0] == F32(float(r1))
+        steps += 1
+    assert steps == len(rows) - 1 >= 3
 
 
 @pytest.mark.parametrize("warmup_n", [0, 1, 2, 5])
@@ -510,7 +519,9 @@ def test_warmup_is_ssgd_and_hands_over_to_formal_training(oracle, warmup_n):
     rng = np.random.default_rng(30 + warmup_n)
     n, N, k, t, lr_l, lr_g = 41, 4, 3, 0.5, 0.25, 0.125
     w0 = (rng.integers(-2048, 2048, n) / 64.0).astype(np.float32)
-    sim = oracle.TrainerSimulation(w0, N, warmup_n, k, t, lr_l, lr_g, self_rank=2)
+    # the local buffer starts at a sentinel unrelated to W0: Alg. 1 never reads it before writing it
+    sentinel = np.full(n, -1234.5, np.float32)
+    sim = oracle.TrainerSimulation(w0, N, warmup_n, k, t, lr_l, lr_g, self_rank=2, w_local0=sentinel)
     ref = w0.astype(np.float64)
     modes = []
     for it in range(warmup_n + 1 + 2 * k):
@@ -530,7 +541,8 @@ def test_warmup_is_ssgd_and_hands_over_to_formal_training(oracle, warmup_n):
                 assert np.array_equal(sim.w_local.astype(np.float64),
                                       w_before.astype(np.float64) - lr_l * grads[2].astype(np.float64))
             else:
-                assert np.array_equal(sim.w_local, loc_before)                   # untouched before n-1
+                assert np.array_equal(sim.w_local, sentinel)                     # untouched before n-1
+                assert np.array_equal(sim.w_local, loc_before)
         else:
             # formal training: local weights from the pre-pass global weights, own 32-bit gradient
             assert np.array_equal(sim.w_local.astype(np.float64),
