@@ -18,10 +18,10 @@
  *              except that a plan keeps (borrows) the pointers it was built from.
  *   alignment  fp32 buffers must be 16-byte aligned, packed buffers 4-byte
  *              aligned (CDSGD_ERR_ALIGN otherwise).
- *   aliasing   Within one call or one tensor of a plan, an output buffer must not
- *              overlap an input or another output (w_local / w_global, residual /
- *              grad, ...): CDSGD_ERR_ALIAS.  Buffers of different tensors and the
- *              peers' streams are not cross-checked.
+ *   aliasing   Within one call or one tensor of a layer list, an output buffer
+ *              (residual, w_global, w_local, packed_self, packed, agg) must not overlap
+ *              an input or another output, the peers' streams of that tensor included:
+ *              CDSGD_ERR_ALIAS.  Buffers of different tensors are not cross-checked.
  *   stream     hip_stream is a hipStream_t passed as void* (NULL = the null
  *              stream).  Work is enqueued and the call returns; nothing
  *              synchronises.
@@ -66,6 +66,11 @@ size_t cdsgd_packed_words(size_t n);
 
 /* Static, NUL-terminated description of a status code. */
 const char *cdsgd_status_string(int status);
+
+/* Static, NUL-terminated identity (16 hex digits) of the sources, headers and compiler flags
+ * this library was built from, as computed by the build script; lets a harness tell a stale
+ * library from a current one.  Not part of the method. */
+const char *cdsgd_build_id(void);
 
 /*
  * Quantise and pack one worker's gradient (Sec. 2.3, Sec. 3.4.1, Sec. 3.2.2).
@@ -213,8 +218,9 @@ int cdsgd_step_global(cdsgd_plan *plan, long step, int k, float threshold, float
  *               pointers to fp32[n] (what the server would receive); row `self` is
  *               ignored (the own gradient is cdsgd_tensor.grad) and may be NULL.
  * Copies the pointers to the device (allocates on first use, synchronous copy);
- * the plan borrows the buffers.  May be called again to rebind.  With
- * num_workers == 1 nothing is needed and the call is a no-op.
+ * the plan borrows the buffers.  May be called again to rebind: that rewrites the
+ * pointer table the kernels read, so do not call it while a pass of this plan may
+ * still be running.  With num_workers == 1 nothing is needed and the call is a no-op.
  */
 int cdsgd_plan_bind_full_grads(cdsgd_plan *plan, const float *const *const *peer_grads);
 

@@ -63,6 +63,8 @@ def lib():
         L.cdsgd_packed_words.argtypes = [sz]
         L.cdsgd_status_string.restype = ctypes.c_char_p
         L.cdsgd_status_string.argtypes = [i]
+        L.cdsgd_build_id.restype = ctypes.c_char_p
+        L.cdsgd_build_id.argtypes = []
         L.cdsgd_quantize_pack.restype = i
         L.cdsgd_quantize_pack.argtypes = [vp, vp, vp, sz, f, vp]
         L.cdsgd_decode_sum.restype = i
@@ -180,6 +182,39 @@ def cdsgd_cost_period_mean(tau, phi, psi, delta, k) -> dict:
     return out.as_dict()
 
 
+def _marshal_layer_list(tensors, peers, num_workers, grad_dtype):
+    """The C arrays of a layer list: (cdsgd_tensor[T], peers' row table or None, keep-alive list)."""
+    T = len(tensors)
+    if grad_dtype not in GRAD_DTYPES:
+        raise TypeError("gradients must be float32, bfloat16 or float16")
+    arr = (cdsgd_tensor * max(T, 1))()
+    for i, t in enumerate(tensors):
+        n = t["w_global"].numel()
+        arr[i].w_global = _dev(t["w_global"], torch.float32, None, "w_global").value
+        arr[i].w_local = _dev(t["w_local"], torch.float32, n, "w_local").value
+        arr[i].residual = _dev(t["residual"], torch.float32, n, "residual").value
+        arr[i].grad = _dev(t["grad"], grad_dtype, n, "grad").value
+        arr[i].packed_self = _dev(t["packed_self"], PACKED_DTYPE, packed_words(n), "packed_self").value
+        af = t.get("agg_full")
+        arr[i].agg_full = _dev(af, torch.float32, n, "agg_full").value if af is not None else None
+        arr[i].n = n
+    if peers is None:
+        return arr, None, []
+    rows = (ctypes.POINTER(ctypes.c_void_p) * max(num_workers, 1))()
+    keep = []
+    for j in range(num_workers):
+        if peers[j] is None:
+            rows[j] = ctypes.POINTER(ctypes.c_void_p)()
+            continue
+        row = (ctypes.c_void_p * max(T, 1))()
+        for i in range(T):
+            n = tensors[i]["w_global"].numel()
+            row[i] = _dev(peers[j][i], PACKED_DTYPE, packed_words(n), "peers[%d][%d]" % (j, i)).value
+        keep.append(row)
+        rows[j] = ctypes.cast(row, ctypes.POINTER(ctypes.c_void_p))
+    return arr, rows, keep
+
+
 class Plan:
     """A fused-step plan over a layer list (cdsgd_plan_create / cdsgd_step_fused / cdsgd_plan_destroy).
 
@@ -191,42 +226,16 @@ class Plan:
 
     def __init__(self, tensors, peers, num_workers, self_rank, grad_dtype=torch.float32):
         T = len(tensors)
-        if grad_dtype not in GRAD_DTYPES:
-            raise TypeError("gradients must be float32, bfloat16 or float16")
         self._grad_dtype = grad_dtype
         self._keep = (tensors, peers)
-        arr = (cdsgd_tensor * max(T, 1))()
-        for i, t in enumerate(tensors):
-            n = t["w_global"].numel()
-            arr[i].w_global = _dev(t["w_global"], torch.float32, None, "w_global").value
-            arr[i].w_local = _dev(t["w_local"], torch.float32, n, "w_local").value
-            arr[i].residual = _dev(t["residual"], torch.float32, n, "residual").value
-            arr[i].grad = _dev(t["grad"], grad_dtype, n, "grad").value
-            arr[i].packed_self = _dev(t["packed_self"], PACKED_DTYPE, packed_words(n), "packed_self").value
-            af = t.get("agg_full")
-            arr[i].agg_full = _dev(af, torch.float32, n, "agg_full").value if af is not None else None
-            arr[i].n = n
-        rows = (ctypes.POINTER(ctypes.c_void_p) * max(num_workers, 1))()
-        self._rows = []
-        if peers is not None:
-            for j in range(num_workers):
-                if peers[j] is None:
-                    rows[j] = ctypes.POINTER(ctypes.c_void_p)()
-                    continue
-                row = (ctypes.c_void_p * max(T, 1))()
-                for i in range(T):
-                    n = tensors[i]["w_global"].numel()
-                    row[i] = _dev(peers[j][i], PACKED_DTYPE, packed_words(n), "peers[%d][%d]" % (j, i)).value
-                self._rows.append(row)
-                rows[j] = ctypes.cast(row, ctypes.POINTER(ctypes.c_void_p))
+        arr, rows, self._rows = _marshal_layer_list(tensors, peers, num_workers, grad_dtype)
         self._sizes = [t["w_global"].numel() for t in tensors]
         handle = ctypes.c_void_p()
         if grad_dtype == torch.float32:
-            st = lib().cdsgd_plan_create(arr, T, rows if peers is not None else None, int(num_workers),
-                                         int(self_rank), ctypes.byref(handle))
+            st = lib().cdsgd_plan_create(arr, T, rows, int(num_workers), int(self_rank), ctypes.byref(handle))
         else:
-            st = lib().cdsgd_plan_create_typed(arr, T, rows if peers is not None else None, int(num_workers),
-                                               int(self_rank), GRAD_DTYPES[grad_dtype], ctypes.byref(handle))
+            st = lib().cdsgd_plan_create_typed(arr, T, rows, int(num_workers), int(self_rank),
+                                               GRAD_DTYPES[grad_dtype], ctypes.byref(handle))
         _check(st, "cdsgd_plan_create")
         self._handle = handle
         self.num_workers = int(num_workers)

@@ -1,5 +1,7 @@
 """Build libcdsgd.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree."""
+import hashlib
 import os
+import re
 import shutil
 import subprocess
 import sys
@@ -29,9 +31,34 @@ def hipcc_path() -> str:
     return p
 
 
+def source_id(extra_flags=()) -> str:
+    """Identity of what a build is made from: the sources, the headers and the flags (16 hex digits).
+    It is compiled into the library (cdsgd_build_id) so that a library can be matched to the tree."""
+    h = hashlib.sha256()
+    headers = sorted(os.path.join(INCLUDE, f) for f in os.listdir(INCLUDE) if f.endswith(".h"))
+    for path in [SRC, *SRC_HOST, *headers]:
+        h.update(os.path.basename(path).encode() + b"\0")
+        with open(path, "rb") as fh:
+            h.update(fh.read())
+        h.update(b"\0")
+    h.update(" ".join([*HIPCC_FLAGS, *extra_flags]).encode())
+    return h.hexdigest()[:16]
+
+
+def built_id(path=LIB):
+    """The source identity a built library carries, or None (no library, or one without an identity)."""
+    try:
+        with open(path, "rb") as fh:
+            m = re.search(rb"CDSGD_BUILD_ID=([0-9a-f]{16})", fh.read())
+    except OSError:
+        return None
+    return m.group(1).decode() if m else None
+
+
 def build(extra_flags=(), out=LIB, verbose=False) -> str:
     tmp = out + ".tmp%d" % os.getpid()
-    cmd = [hipcc_path(), *HIPCC_FLAGS, *extra_flags, "-I", INCLUDE, SRC, *SRC_HOST, "-o", tmp]
+    cmd = [hipcc_path(), *HIPCC_FLAGS, *extra_flags, '-DCDSGD_BUILD_ID_HEX="%s"' % source_id(extra_flags),
+           "-I", INCLUDE, SRC, *SRC_HOST, "-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -46,9 +73,13 @@ def build(extra_flags=(), out=LIB, verbose=False) -> str:
 
 
 def ensure_built() -> str:
-    """Build only if no library is there (tests, the smoke check and the benchmark call this;
-    the binding itself never builds and never falls back)."""
-    return LIB if os.path.exists(LIB) else build()
+    """Build if no library is there or if the one that is there was made from other sources,
+    headers or flags than the tree now holds (tests, the smoke check and the benchmark call this;
+    the binding itself never builds and never falls back).  The comparison is by content, not by
+    file time, so a tree that was copied elsewhere together with its library is not rebuilt."""
+    if os.path.exists(LIB) and built_id(LIB) == source_id():
+        return LIB
+    return build()
 
 
 if __name__ == "__main__":

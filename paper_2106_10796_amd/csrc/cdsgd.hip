@@ -748,6 +748,11 @@ inline bool is_pow2_threshold(float t)
 
 inline bool good_threshold(float t) { return std::isfinite(t) && t > 0.0f; }
 
+inline bool good_step_params(long step, int k, float threshold, float lr_local, float lr_global)
+{
+    return k >= 1 && step >= 0 && good_threshold(threshold) && std::isfinite(lr_local) && std::isfinite(lr_global);
+}
+
 inline int launch_status()
 {
     return hipGetLastError() == hipSuccess ? CDSGD_OK : CDSGD_ERR_DEVICE;
@@ -755,21 +760,26 @@ inline int launch_status()
 
 }  // namespace
 
-struct cdsgd_plan {
-    void *device_block = nullptr;  // one allocation: tensors, chunks, peer pointers
+// What a pass needs to know about a layer list: device tables and a few host-side facts.
+struct PlanTables {
     TensorDesc *tensors = nullptr;
     ChunkRef *chunks = nullptr;
-    const uint8_t **peers = nullptr;
+    const uint8_t **peers = nullptr;    // [num_tensors][num_workers - 1]
+    const void **peer_grads = nullptr;  // same shape, or null: correction passes read agg_full
     int num_tensors = 0;
     int num_workers = 0;
     int self = 0;
     unsigned num_chunks = 0;
     bool has_agg_full = false;
-    const void **peer_grads = nullptr;  // second allocation, made by cdsgd_plan_bind_full_grads
-    int grad_type = kGradF32;           // element type of grad and of the bound peer gradients
+    int grad_type = kGradF32;          // element type of grad and of the bound peer gradients
+    bool own_thresholds = false;       // every tensor carries its own threshold
+    bool own_thresholds_pow2 = false;  // ... and all of them are powers of two
+};
+
+struct cdsgd_plan : PlanTables {
+    void *device_block = nullptr;          // one allocation: tensors, chunks, peer pointers
+    void *peer_grads_block = nullptr;      // second allocation, made by cdsgd_plan_bind_full_grads
     std::vector<TensorDesc> host_tensors;  // host copy of the descriptor table (for cdsgd_plan_set_thresholds)
-    bool own_thresholds = false;           // every tensor carries its own threshold
-    bool own_thresholds_pow2 = false;      // ... and all of them are powers of two
 };
 
 struct cdsgd_trainer {
@@ -782,8 +792,78 @@ struct cdsgd_trainer {
 
 namespace {
 
+// Host-side checks of a layer list and its peers (no HIP call).  Returns the number of chunks and whether every tensor
+// has an agg_full buffer.
+int check_layer_list(const cdsgd_tensor *tensors, int num_tensors, const uint32_t *const *const *peers,
+                     int num_workers, int self, int grad_dtype, unsigned long long *total_chunks_out,
+                     bool *all_agg_out)
+{
+    if (!tensors) return CDSGD_ERR_NULL;
+    if (grad_dtype != CDSGD_GRAD_F32 && grad_dtype != CDSGD_GRAD_BF16 && grad_dtype != CDSGD_GRAD_F16)
+        return CDSGD_ERR_PARAM;
+    const size_t grad_elem = grad_dtype == CDSGD_GRAD_F32 ? 4 : 2;
+    if (num_tensors < 1) return CDSGD_ERR_SIZE;
+    if (num_workers < 1 || num_workers > CDSGD_MAX_WORKERS || self < 0 || self >= num_workers)
+        return CDSGD_ERR_WORKERS;
+    if (num_workers > 1 && !peers) return CDSGD_ERR_NULL;
+    unsigned long long total_chunks = 0;
+    bool all_agg = true;
+    for (int i = 0; i < num_tensors; ++i) {
+        const cdsgd_tensor &t = tensors[i];
+        if (!t.w_global || !t.w_local || !t.residual || !t.grad || !t.packed_self) return CDSGD_ERR_NULL;
+        if (t.n == 0 || chunks_of(t.n) > kMaxGrid) return CDSGD_ERR_SIZE;
+        if (!aligned(t.w_global, 16) || !aligned(t.w_local, 16) || !aligned(t.residual, 16) ||
+            !aligned(t.grad, 16) || !aligned(t.agg_full, 16) || !aligned(t.packed_self, 4))
+            return CDSGD_ERR_ALIGN;
+        const size_t fb = t.n * sizeof(float), gb = t.n * grad_elem, pb = (size_t)packed_bytes_of(t.n);
+        if (overlap(t.w_global, t.w_local, fb) || overlap(t.w_global, t.residual, fb) ||
+            overlap(t.w_local, t.residual, fb) || overlap(t.agg_full, t.w_global, fb) ||
+            overlap(t.agg_full, t.w_local, fb) || overlap2(t.grad, gb, t.residual, fb) ||
+            overlap2(t.grad, gb, t.w_global, fb) || overlap2(t.grad, gb, t.w_local, fb) ||
+            overlap2(t.packed_self, pb, t.w_global, fb) || overlap2(t.packed_self, pb, t.w_local, fb) ||
+            overlap2(t.packed_self, pb, t.residual, fb) || overlap2(t.packed_self, pb, t.grad, gb) ||
+            overlap2(t.packed_self, pb, t.agg_full, fb))
+            return CDSGD_ERR_ALIAS;
+        all_agg = all_agg && t.agg_full != nullptr;
+        total_chunks += chunks_of(t.n);
+        if (total_chunks > kMaxGrid) return CDSGD_ERR_SIZE;
+    }
+    for (int j = 0; j < num_workers; ++j) {
+        if (j == self) continue;
+        if (!peers[j]) return CDSGD_ERR_NULL;
+        for (int i = 0; i < num_tensors; ++i) {
+            if (!peers[j][i]) return CDSGD_ERR_NULL;
+            if (!aligned(peers[j][i], 4)) return CDSGD_ERR_ALIGN;
+            // a peer's stream is read while this tensor's outputs are written
+            const cdsgd_tensor &t = tensors[i];
+            const size_t fb = t.n * sizeof(float), pb = (size_t)packed_bytes_of(t.n);
+            if (overlap2(peers[j][i], pb, t.w_global, fb) || overlap2(peers[j][i], pb, t.w_local, fb) ||
+                overlap2(peers[j][i], pb, t.residual, fb) || overlap2(peers[j][i], pb, t.packed_self, pb))
+                return CDSGD_ERR_ALIAS;
+        }
+    }
+    *total_chunks_out = total_chunks;
+    *all_agg_out = all_agg;
+    return CDSGD_OK;
+}
+
+TensorDesc make_desc(const cdsgd_tensor &t)
+{
+    TensorDesc d;
+    d.w_global = t.w_global;
+    d.w_local = t.w_local;
+    d.residual = t.residual;
+    d.grad = t.grad;
+    d.packed_self = reinterpret_cast<uint8_t *>(t.packed_self);
+    d.agg_full = t.agg_full;
+    d.ext = extent_of(t.n);
+    d.threshold = 0.0f;
+    d.pad_ = 0;
+    return d;
+}
+
 // Launch one full-gradient pass (see k_fused_full) for a plan.
-int launch_full_pass(cdsgd_plan *plan, int local_mode, float lr_local, float lr_global, void *hip_stream)
+int launch_full_pass(const PlanTables *plan, int local_mode, float lr_local, float lr_global, void *hip_stream)
 {
     const bool sum = plan->peer_grads != nullptr || plan->num_workers == 1;
     if (!sum && !plan->has_agg_full) return CDSGD_ERR_NULL;
@@ -816,9 +896,20 @@ int launch_full_pass(cdsgd_plan *plan, int local_mode, float lr_local, float lr_
 
 }  // namespace
 
+#ifndef CDSGD_BUILD_ID_HEX
+#define CDSGD_BUILD_ID_HEX "0000000000000000"
+#endif
+
 extern "C" {
 
 size_t cdsgd_packed_words(size_t n) { return (n + 15) / 16; }
+
+// The marker in front makes the identity findable in the file without loading it.
+const char *cdsgd_build_id(void)
+{
+    static const char id[] = "CDSGD_BUILD_ID=" CDSGD_BUILD_ID_HEX;
+    return id + 15;
+}
 
 const char *cdsgd_status_string(int status)
 {
@@ -842,7 +933,10 @@ int cdsgd_quantize_pack(const float *grad, float *residual, uint32_t *packed, si
     if (n == 0 || chunks_of(n) > kMaxGrid) return CDSGD_ERR_SIZE;
     if (!good_threshold(threshold)) return CDSGD_ERR_PARAM;
     if (!aligned(grad, 16) || !aligned(residual, 16) || !aligned(packed, 4)) return CDSGD_ERR_ALIGN;
-    if (overlap(grad, residual, n * sizeof(float))) return CDSGD_ERR_ALIAS;
+    if (overlap(grad, residual, n * sizeof(float)) ||
+        overlap2(packed, (size_t)packed_bytes_of(n), grad, n * sizeof(float)) ||
+        overlap2(packed, (size_t)packed_bytes_of(n), residual, n * sizeof(float)))
+        return CDSGD_ERR_ALIAS;
     const unsigned grid = (unsigned)chunks_of(n);
     hipLaunchKernelGGL(k_quantize_pack, dim3(grid), dim3(kBlock), 0, (hipStream_t)hip_stream, grad, residual,
                        reinterpret_cast<uint8_t *>(packed), extent_of(n), threshold);
@@ -861,6 +955,8 @@ int cdsgd_decode_sum(const uint32_t *const *packed, int num_workers, float *agg,
     if (!aligned(agg, 16)) return CDSGD_ERR_ALIGN;
     for (int j = 0; j < num_workers; ++j)
         if (!aligned(packed[j], 4)) return CDSGD_ERR_ALIGN;
+    for (int j = 0; j < num_workers; ++j)
+        if (overlap2(packed[j], (size_t)packed_bytes_of(n), agg, n * sizeof(float))) return CDSGD_ERR_ALIAS;
     StreamTable tab;
     std::memset(&tab, 0, sizeof(tab));
     for (int j = 0; j < num_workers; ++j) tab.p[j] = reinterpret_cast<const uint8_t *>(packed[j]);
@@ -916,42 +1012,11 @@ int cdsgd_plan_create_typed(const cdsgd_tensor *tensors, int num_tensors, const 
 {
     if (!out) return CDSGD_ERR_NULL;
     *out = nullptr;
-    if (!tensors) return CDSGD_ERR_NULL;
-    if (grad_dtype != CDSGD_GRAD_F32 && grad_dtype != CDSGD_GRAD_BF16 && grad_dtype != CDSGD_GRAD_F16)
-        return CDSGD_ERR_PARAM;
-    const size_t grad_elem = grad_dtype == CDSGD_GRAD_F32 ? 4 : 2;
-    if (num_tensors < 1) return CDSGD_ERR_SIZE;
-    if (num_workers < 1 || num_workers > CDSGD_MAX_WORKERS || self < 0 || self >= num_workers)
-        return CDSGD_ERR_WORKERS;
-    if (num_workers > 1 && !peers) return CDSGD_ERR_NULL;
     unsigned long long total_chunks = 0;
     bool all_agg = true;
-    for (int i = 0; i < num_tensors; ++i) {
-        const cdsgd_tensor &t = tensors[i];
-        if (!t.w_global || !t.w_local || !t.residual || !t.grad || !t.packed_self) return CDSGD_ERR_NULL;
-        if (t.n == 0 || chunks_of(t.n) > kMaxGrid) return CDSGD_ERR_SIZE;
-        if (!aligned(t.w_global, 16) || !aligned(t.w_local, 16) || !aligned(t.residual, 16) ||
-            !aligned(t.grad, 16) || !aligned(t.agg_full, 16) || !aligned(t.packed_self, 4))
-            return CDSGD_ERR_ALIGN;
-        const size_t fb = t.n * sizeof(float), gb = t.n * grad_elem;
-        if (overlap(t.w_global, t.w_local, fb) || overlap(t.w_global, t.residual, fb) ||
-            overlap(t.w_local, t.residual, fb) || overlap(t.agg_full, t.w_global, fb) ||
-            overlap(t.agg_full, t.w_local, fb) || overlap2(t.grad, gb, t.residual, fb) ||
-            overlap2(t.grad, gb, t.w_global, fb) || overlap2(t.grad, gb, t.w_local, fb))
-            return CDSGD_ERR_ALIAS;
-        all_agg = all_agg && t.agg_full != nullptr;
-        total_chunks += chunks_of(t.n);
-        if (total_chunks > kMaxGrid) return CDSGD_ERR_SIZE;
-    }
+    const int rc = check_layer_list(tensors, num_tensors, peers, num_workers, self, grad_dtype, &total_chunks, &all_agg);
+    if (rc != CDSGD_OK) return rc;
     const int num_peers = num_workers - 1;
-    for (int j = 0; j < num_workers; ++j) {
-        if (j == self) continue;
-        if (!peers[j]) return CDSGD_ERR_NULL;
-        for (int i = 0; i < num_tensors; ++i) {
-            if (!peers[j][i]) return CDSGD_ERR_NULL;
-            if (!aligned(peers[j][i], 4)) return CDSGD_ERR_ALIGN;
-        }
-    }
 
     // host image of the device block
     const size_t bytes_t = sizeof(TensorDesc) * (size_t)num_tensors;
@@ -967,15 +1032,7 @@ int cdsgd_plan_create_typed(const cdsgd_tensor *tensors, int num_tensors, const 
     size_t ci = 0;
     for (int i = 0; i < num_tensors; ++i) {
         const cdsgd_tensor &t = tensors[i];
-        ht[i].w_global = t.w_global;
-        ht[i].w_local = t.w_local;
-        ht[i].residual = t.residual;
-        ht[i].grad = t.grad;
-        ht[i].packed_self = reinterpret_cast<uint8_t *>(t.packed_self);
-        ht[i].agg_full = t.agg_full;
-        ht[i].ext = extent_of(t.n);
-        ht[i].threshold = 0.0f;
-        ht[i].pad_ = 0;
+        ht[i] = make_desc(t);
         const unsigned nc = (unsigned)chunks_of(t.n);
         for (unsigned c = 0; c < nc; ++c) {
             hc[ci].tensor = (unsigned)i;
@@ -1026,7 +1083,7 @@ int cdsgd_plan_destroy(cdsgd_plan *plan)
         (void)hipGetLastError();
         rc = CDSGD_ERR_DEVICE;
     }
-    if (plan->peer_grads && hipFree((void *)plan->peer_grads) != hipSuccess) {
+    if (plan->peer_grads_block && hipFree(plan->peer_grads_block) != hipSuccess) {
         (void)hipGetLastError();
         rc = CDSGD_ERR_DEVICE;
     }
@@ -1037,12 +1094,11 @@ int cdsgd_plan_destroy(cdsgd_plan *plan)
 namespace {
 
 // One pass of FormalTraining's loop; with_local = false leaves eq. 11 out (split form).
-int launch_formal_pass(cdsgd_plan *plan, long step, int k, float threshold, float lr_local, float lr_global,
+int launch_formal_pass(const PlanTables *plan, long step, int k, float threshold, float lr_local, float lr_global,
                        bool with_local, void *hip_stream)
 {
     if (!plan) return CDSGD_ERR_NULL;
-    if (k < 1 || step < 0 || !good_threshold(threshold) || !std::isfinite(lr_local) || !std::isfinite(lr_global))
-        return CDSGD_ERR_PARAM;
+    if (!good_step_params(step, k, threshold, lr_local, lr_global)) return CDSGD_ERR_PARAM;
     const bool compressed = (step % k) != 0;
     if (!compressed)
         return launch_full_pass(plan, with_local ? kLocalRule : kLocalNone, lr_local, lr_global, hip_stream);
@@ -1119,16 +1175,17 @@ int cdsgd_plan_bind_full_grads(cdsgd_plan *plan, const float *const *const *peer
         ++slot;
     }
     const size_t bytes = image.size() * sizeof(const void *);
-    void *dev = (void *)plan->peer_grads;
+    void *dev = plan->peer_grads_block;
     if (!dev && hipMalloc(&dev, bytes) != hipSuccess) {
         (void)hipGetLastError();
         return CDSGD_ERR_DEVICE;
     }
     if (hipMemcpy(dev, image.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
         (void)hipGetLastError();
-        if (!plan->peer_grads) (void)hipFree(dev);
+        if (!plan->peer_grads_block) (void)hipFree(dev);
         return CDSGD_ERR_DEVICE;
     }
+    plan->peer_grads_block = dev;
     plan->peer_grads = (const void **)dev;
     return CDSGD_OK;
 }
@@ -1217,3 +1274,4 @@ int cdsgd_trainer_destroy(cdsgd_trainer *trainer)
 }
 
 }  // extern "C"
+

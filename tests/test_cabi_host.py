@@ -14,8 +14,7 @@ HEADERS = [os.path.join(ROOT, "include", "cdsgd.h"), os.path.join(ROOT, "include
 @pytest.fixture(scope="module")
 def L():
     from paper_2106_10796_amd import binding, build
-    if not os.path.exists(binding.LIB_PATH):
-        build.build()
+    build.ensure_built()
     return binding.lib()
 
 
@@ -39,6 +38,24 @@ def test_header_declares_the_named_entry_points():
 def test_library_exports_every_declared_symbol(L):
     for name in declared_functions():
         assert hasattr(L, name), name
+
+
+def test_library_matches_the_tree(L, monkeypatch):
+    """The library carries the identity of the sources, headers and flags it was built from;
+    ensure_built() rebuilds exactly when that differs from what the tree holds now."""
+    from paper_2106_10796_amd import build
+    now = build.source_id()
+    assert re.fullmatch(r"[0-9a-f]{16}", now)
+    assert build.built_id() == now == L.cdsgd_build_id().decode()
+    assert build.source_id(("-DSOMETHING",)) != now               # flags are part of the identity
+    calls = []
+    monkeypatch.setattr(build, "build", lambda *a, **k: calls.append(1) or build.LIB)
+    build.ensure_built()
+    assert calls == []                                            # current: loaded as it is
+    monkeypatch.setattr(build, "source_id", lambda extra_flags=(): "f" * 16)
+    build.ensure_built()
+    assert calls == [1]                                           # stale: rebuilt
+    assert build.built_id(os.path.join(ROOT, "include", "cdsgd.h")) is None
 
 
 def test_packed_words(L):
@@ -174,8 +191,19 @@ def test_aliasing_is_refused(L):
         for k, v in kw.items():
             setattr(t, k, v)
         return (cdsgd_tensor * 1)(t)
-    for bad in (dict(w_local=B1), dict(residual=B4), dict(grad=B1 + 64), dict(w_local=B3), dict(agg_full=B2)):
+    for bad in (dict(w_local=B1), dict(residual=B4), dict(grad=B1 + 64), dict(w_local=B3), dict(agg_full=B2),
+                dict(packed_self=B3 + 4 * n - 4), dict(packed_self=B1), dict(packed_self=B4 + 16),
+                dict(packed_self=B6)):                      # own codes on a peer's stream
         assert L.cdsgd_plan_create(tensor(**bad), 1, rows, 2, 0, ctypes.byref(out)) == ERR_ALIAS
+    row_on_w = (ctypes.c_void_p * 1)(B1 + 32)                # a peer's stream inside w_global
+    rows_on_w = (ctypes.POINTER(ctypes.c_void_p) * 2)(ctypes.POINTER(ctypes.c_void_p)(),
+                                                      ctypes.cast(row_on_w, ctypes.POINTER(ctypes.c_void_p)))
+    assert L.cdsgd_plan_create(tensor(), 1, rows_on_w, 2, 0, ctypes.byref(out)) == ERR_ALIAS
+    # the single-tensor calls: packed on grad / residual, agg on a packed stream
+    assert L.cdsgd_quantize_pack(B1, B2, B1 + 8, n, 0.5, None) == ERR_ALIAS
+    assert L.cdsgd_quantize_pack(B1, B2, B2 + 4 * n - 4, n, 0.5, None) == ERR_ALIAS
+    two = (ctypes.c_void_p * 2)(B1, B2 + 4)
+    assert L.cdsgd_decode_sum(two, 2, B2, n, 0.5, None) == ERR_ALIAS
     # a 16-bit gradient buffer is half as long: a residual right behind it is fine for bf16, not for fp32
     tight = dict(grad=B4, residual=B4 + 2 * n + 48)       # 2n bytes of bf16, next 16-byte boundary
     assert L.cdsgd_plan_create(tensor(**tight), 1, rows, 2, 0, ctypes.byref(out)) == ERR_ALIAS
