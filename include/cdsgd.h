@@ -262,6 +262,38 @@ int cdsgd_trainer_step(cdsgd_trainer *trainer, void *hip_stream, int *pass_kind)
 long cdsgd_trainer_iteration(const cdsgd_trainer *trainer);
 int cdsgd_trainer_destroy(cdsgd_trainer *trainer);
 
+/*
+ * cdsgd_step_fused for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same pass, same results
+ * and same argument checks as cdsgd_plan_create_typed followed by cdsgd_step_fused on that
+ * plan, but no plan: the layer list and the peers' pointers are passed on every call, and
+ * the tables a plan would keep in memory of its own (tensor descriptors, chunk table,
+ * peers' pointer table) are written, on `hip_stream` and by small kernels whose data travel
+ * in their arguments, into one static device array of about 4.6 MiB that the library holds
+ * on every GPU it runs on until the process ends.  The call makes no allocation, free or
+ * host-to-device copy call; the first call on a device looks up the array's address (make
+ * that call outside a graph capture).
+ *   limits      num_tensors <= CDSGD_STATIC_MAX_TENSORS and
+ *               sum over tensors of ceil(n / CDSGD_STATIC_CHUNK_ELEMS) <= CDSGD_STATIC_MAX_CHUNKS
+ *               (up to 2^31 elements in all): CDSGD_ERR_SIZE beyond that.
+ *   correction  passes (step % k == 0) read agg_full of every tensor (CDSGD_ERR_NULL if one is
+ *               missing and num_workers > 1); bound full gradients and per-tensor thresholds are
+ *               features of a plan and are not available here.
+ *   sharing     every call on a GPU uses that GPU's one array: calls on the same stream are
+ *               ordered and safe; calls that may overlap on one GPU (different streams, or
+ *               different host threads on different streams) race on the tables and must be
+ *               ordered by the caller.  Plans are not affected.
+ * The tables are rebuilt on every call (a few small launches before the pass itself), so a
+ * plan remains the faster form for a layer list that is stepped many times.
+ */
+#define CDSGD_STATIC_MAX_TENSORS 1024
+#define CDSGD_STATIC_MAX_CHUNKS 524288
+#define CDSGD_STATIC_CHUNK_ELEMS 4096
+int cdsgd_step_fused_static(const cdsgd_tensor *tensors, int num_tensors,
+                            const uint32_t *const *const *peers, int num_workers, int self,
+                            int grad_dtype, long step, int k, float threshold, float lr_local,
+                            float lr_global, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

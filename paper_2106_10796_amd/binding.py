@@ -13,6 +13,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libcdsgd.so")
 
 MAX_WORKERS = 64
+STATIC_MAX_TENSORS, STATIC_MAX_CHUNKS, STATIC_CHUNK_ELEMS = 1024, 524288, 4096   # cdsgd_step_fused_static
 PASS_WARMUP, PASS_COMPRESSED, PASS_CORRECTION = 0, 1, 2
 GRAD_DTYPES = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}   # cdsgd_grad_dtype
 OK, ERR_NULL, ERR_SIZE, ERR_PARAM, ERR_ALIGN, ERR_WORKERS, ERR_DEVICE, ERR_ALIAS = range(8)
@@ -99,6 +100,9 @@ def lib():
         L.cdsgd_trainer_iteration.argtypes = [vp]
         L.cdsgd_trainer_destroy.restype = i
         L.cdsgd_trainer_destroy.argtypes = [vp]
+        L.cdsgd_step_fused_static.restype = i
+        L.cdsgd_step_fused_static.argtypes = [ctypes.POINTER(cdsgd_tensor), i, ctypes.POINTER(ctypes.POINTER(vp)),
+                                              i, i, i, ctypes.c_long, i, f, f, f, vp]
         L.cdsgd_cost_iteration.restype = i
         L.cdsgd_cost_iteration.argtypes = [ctypes.POINTER(cdsgd_cost_params), ctypes.c_long,
                                            ctypes.POINTER(cdsgd_cost)]
@@ -213,6 +217,17 @@ def _marshal_layer_list(tensors, peers, num_workers, grad_dtype):
         keep.append(row)
         rows[j] = ctypes.cast(row, ctypes.POINTER(ctypes.c_void_p))
     return arr, rows, keep
+
+
+def cdsgd_step_fused_static(tensors, peers, num_workers, self_rank, step, k, threshold, lr_local, lr_global,
+                            grad_dtype=torch.float32):
+    """One fused pass over a layer list without a plan and without any allocation in the library
+    (cdsgd_step_fused_static); tensors and peers as for Plan."""
+    arr, rows, _keep = _marshal_layer_list(tensors, peers, num_workers, grad_dtype)
+    st = lib().cdsgd_step_fused_static(arr, len(tensors), rows, int(num_workers), int(self_rank),
+                                       GRAD_DTYPES[grad_dtype], int(step), int(k), float(threshold),
+                                       float(lr_local), float(lr_global), _stream())
+    _check(st, "cdsgd_step_fused_static")
 
 
 class Plan:

@@ -20,6 +20,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -699,6 +700,66 @@ __global__ __launch_bounds__(CDSGD_BLOCK) void k_fused_full(const TensorDesc *__
 }
 
 // ---------------------------------------------------------------------------
+// tables built on the device, for the entry point that allocates nothing
+// ---------------------------------------------------------------------------
+// Up to kStorePayload bytes travel in the kernel arguments and are written to dst.
+constexpr unsigned kStorePayload = 3072;
+struct StorePayload {
+    uint4 q[kStorePayload / 16];
+};
+
+__global__ __launch_bounds__(256) void k_static_store(StorePayload p, uint4 *__restrict__ dst, unsigned count16)
+{
+    const unsigned i = threadIdx.x;
+    if (i < count16) dst[i] = p.q[i];
+}
+
+// chunk_start[i] = number of chunks of tensors 0..i-1 (num_tensors + 1 entries, the last one
+// the total).  Slot s of the chunk table belongs to the tensor i with
+// chunk_start[i] <= s < chunk_start[i + 1].
+__global__ __launch_bounds__(256) void k_static_chunks(const unsigned *__restrict__ chunk_start, int num_tensors,
+                                                       ChunkRef *__restrict__ chunks, unsigned total)
+{
+    const unsigned slot = blockIdx.x * 256u + threadIdx.x;
+    if (slot >= total) return;
+    int lo = 0, hi = num_tensors;  // invariant: chunk_start[lo] <= slot < chunk_start[hi]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (chunk_start[mid] <= slot) lo = mid;
+        else hi = mid;
+    }
+    ChunkRef cr;
+    cr.tensor = (unsigned)lo;
+    cr.chunk = slot - chunk_start[lo];
+    chunks[slot] = cr;
+}
+
+// Layout of the static device array: descriptor table, chunk_start, peers' pointer table,
+// chunk table; every region starts on a 256-byte boundary and has room for the 16-byte
+// granularity of k_static_store.
+constexpr size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
+constexpr int kStaticMaxTensors = CDSGD_STATIC_MAX_TENSORS;
+constexpr unsigned kStaticMaxChunks = CDSGD_STATIC_MAX_CHUNKS;
+constexpr size_t kStaticOffDesc = 0;
+constexpr size_t kStaticOffStart = round256(sizeof(TensorDesc) * kStaticMaxTensors + 16);
+constexpr size_t kStaticOffPeers = round256(kStaticOffStart + sizeof(unsigned) * (kStaticMaxTensors + 1) + 16);
+constexpr size_t kStaticOffChunks =
+    round256(kStaticOffPeers + sizeof(void *) * (size_t)kStaticMaxTensors * (CDSGD_MAX_WORKERS - 1) + 16);
+constexpr size_t kStaticBytes = kStaticOffChunks + sizeof(ChunkRef) * (size_t)kStaticMaxChunks;
+#if CDSGD_BLOCK == 512 && CDSGD_QPL == 2
+static_assert(kChunkElems == CDSGD_STATIC_CHUNK_ELEMS, "the header states the chunk size the limit is counted in");
+#endif
+
+}  // namespace
+
+// The tables of cdsgd_step_fused_static live here (about 4.6 MiB on every GPU the library
+// runs on, until the process ends).  In host code this name is only a handle for
+// hipGetSymbolAddress; the device address is looked up once per device (static_scratch).
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+namespace {
+
+// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
@@ -761,6 +822,8 @@ inline int launch_status()
 }  // namespace
 
 // What a pass needs to know about a layer list: device tables and a few host-side facts.
+// A plan owns one (tables in memory it allocated); the entry point that allocates nothing
+// builds one on the stack, its tables in the library's static device array.
 struct PlanTables {
     TensorDesc *tensors = nullptr;
     ChunkRef *chunks = nullptr;
@@ -792,7 +855,8 @@ struct cdsgd_trainer {
 
 namespace {
 
-// Host-side checks of a layer list and its peers (no HIP call).  Returns the number of chunks and whether every tensor
+// Host-side checks of a layer list and its peers (no HIP call): what cdsgd_plan_create_typed
+// and cdsgd_step_fused_static share.  Returns the number of chunks and whether every tensor
 // has an agg_full buffer.
 int check_layer_list(const cdsgd_tensor *tensors, int num_tensors, const uint32_t *const *const *peers,
                      int num_workers, int self, int grad_dtype, unsigned long long *total_chunks_out,
@@ -1275,3 +1339,134 @@ int cdsgd_trainer_destroy(cdsgd_trainer *trainer)
 
 }  // extern "C"
 
+namespace {
+
+std::mutex g_static_mutex;
+constexpr int kStaticMaxDevices = 64;
+unsigned char *g_static_ptr[kStaticMaxDevices] = {};
+
+// Device address of `scratch` on the current device, looked up once per device.
+int static_scratch(unsigned char **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kStaticMaxDevices) {
+        (void)hipGetLastError();
+        return CDSGD_ERR_DEVICE;
+    }
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return CDSGD_ERR_DEVICE;
+        }
+        g_static_ptr[dev] = static_cast<unsigned char *>(p);
+    }
+    *out = g_static_ptr[dev];
+    return CDSGD_OK;
+}
+
+// Streams host bytes into a region of the static array through kernel arguments:
+// no host-to-device copy call, no staging memory, nothing a graph capture could not record.
+struct StaticWriter {
+    hipStream_t stream;
+    unsigned char *dst;  // device address the next flush writes to
+    StorePayload buf;
+    unsigned fill = 0;
+    bool ok = true;
+
+    StaticWriter(hipStream_t s, unsigned char *d) : stream(s), dst(d) {}
+
+    void flush()
+    {
+        if (fill == 0) return;
+        while (fill % 16u) reinterpret_cast<unsigned char *>(&buf)[fill++] = 0;
+        hipLaunchKernelGGL(k_static_store, dim3(1), dim3(256), 0, stream, buf, reinterpret_cast<uint4 *>(dst), fill / 16u);
+        ok = ok && hipGetLastError() == hipSuccess;
+        dst += fill;
+        fill = 0;
+    }
+
+    void put(const void *src, unsigned bytes)
+    {
+        const unsigned char *p = static_cast<const unsigned char *>(src);
+        while (bytes) {
+            const unsigned take = bytes < kStorePayload - fill ? bytes : kStorePayload - fill;
+            std::memcpy(reinterpret_cast<unsigned char *>(&buf) + fill, p, take);
+            fill += take;
+            p += take;
+            bytes -= take;
+            if (fill == kStorePayload) flush();
+        }
+    }
+};
+
+}  // namespace
+
+extern "C" int cdsgd_step_fused_static(const cdsgd_tensor *tensors, int num_tensors,
+                                       const uint32_t *const *const *peers, int num_workers, int self,
+                                       int grad_dtype, long step, int k, float threshold, float lr_local,
+                                       float lr_global, void *hip_stream)
+{
+    unsigned long long total_chunks = 0;
+    bool all_agg = true;
+    int rc = check_layer_list(tensors, num_tensors, peers, num_workers, self, grad_dtype, &total_chunks, &all_agg);
+    if (rc != CDSGD_OK) return rc;
+    if (!good_step_params(step, k, threshold, lr_local, lr_global)) return CDSGD_ERR_PARAM;
+    if (num_tensors > kStaticMaxTensors || total_chunks > kStaticMaxChunks) return CDSGD_ERR_SIZE;
+    const bool compressed = (step % k) != 0;
+    if (!compressed && num_workers > 1 && !all_agg) return CDSGD_ERR_NULL;
+
+    unsigned char *base = nullptr;
+    rc = static_scratch(&base);
+    if (rc != CDSGD_OK) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int num_peers = num_workers - 1;
+
+    // descriptor table
+    StaticWriter w(s, base + kStaticOffDesc);
+    for (int i = 0; i < num_tensors; ++i) {
+        const TensorDesc d = make_desc(tensors[i]);
+        w.put(&d, sizeof(d));
+    }
+    w.flush();
+    // chunk_start: running count of chunks, num_tensors + 1 entries
+    w.dst = base + kStaticOffStart;
+    unsigned start = 0;
+    for (int i = 0; i < num_tensors; ++i) {
+        w.put(&start, sizeof(start));
+        start += (unsigned)chunks_of(tensors[i].n);
+    }
+    w.put(&start, sizeof(start));
+    w.flush();
+    // peers' streams, [tensor][peer], the own row left out (compressed passes only)
+    if (compressed && num_peers > 0) {
+        w.dst = base + kStaticOffPeers;
+        for (int i = 0; i < num_tensors; ++i)
+            for (int j = 0; j < num_workers; ++j) {
+                if (j == self) continue;
+                const uint8_t *ptr = reinterpret_cast<const uint8_t *>(peers[j][i]);
+                w.put(&ptr, sizeof(ptr));
+            }
+        w.flush();
+    }
+    if (!w.ok) return CDSGD_ERR_DEVICE;
+    // chunk table, on the device
+    const unsigned total = (unsigned)total_chunks;
+    hipLaunchKernelGGL(k_static_chunks, dim3((total + 255u) / 256u), dim3(256), 0, s,
+                       reinterpret_cast<const unsigned *>(base + kStaticOffStart), num_tensors,
+                       reinterpret_cast<ChunkRef *>(base + kStaticOffChunks), total);
+    if (hipGetLastError() != hipSuccess) return CDSGD_ERR_DEVICE;
+
+    PlanTables pt;
+    pt.tensors = reinterpret_cast<TensorDesc *>(base + kStaticOffDesc);
+    pt.chunks = reinterpret_cast<ChunkRef *>(base + kStaticOffChunks);
+    pt.peers = reinterpret_cast<const uint8_t **>(base + kStaticOffPeers);
+    pt.num_tensors = num_tensors;
+    pt.num_workers = num_workers;
+    pt.self = self;
+    pt.num_chunks = total;
+    pt.has_agg_full = all_agg;
+    pt.grad_type = grad_dtype;
+    return launch_formal_pass(&pt, step, k, threshold, lr_local, lr_global, true, hip_stream);
+}

@@ -170,6 +170,47 @@ def test_plan_and_step_argument_errors(L):
     assert step(fake, 1, 4, 0.5, float("nan"), 0.1, None) == ERR_PARAM
 
 
+def test_step_fused_static_argument_errors(L):
+    """The entry point that allocates nothing checks like plan creation plus a step, and refuses
+    layer lists beyond its static tables, all on the host (fake addresses are never dereferenced)."""
+    from paper_2106_10796_amd.binding import (ERR_ALIGN, ERR_NULL, ERR_PARAM, ERR_SIZE, ERR_WORKERS,
+                                              STATIC_CHUNK_ELEMS, STATIC_MAX_CHUNKS, STATIC_MAX_TENSORS,
+                                              cdsgd_tensor)
+    f = L.cdsgd_step_fused_static
+    arr = (cdsgd_tensor * 1)(_tensor(L))
+    row = (ctypes.c_void_p * 1)(A + 0x70000)
+    rows = (ctypes.POINTER(ctypes.c_void_p) * 2)(ctypes.POINTER(ctypes.c_void_p)(),
+                                                 ctypes.cast(row, ctypes.POINTER(ctypes.c_void_p)))
+    assert f(None, 1, rows, 2, 0, 0, 1, 4, 0.5, 0.1, 0.1, None) == ERR_NULL
+    assert f(arr, 0, rows, 2, 0, 0, 1, 4, 0.5, 0.1, 0.1, None) == ERR_SIZE
+    assert f(arr, 1, rows, 65, 0, 0, 1, 4, 0.5, 0.1, 0.1, None) == ERR_WORKERS
+    assert f(arr, 1, None, 2, 0, 0, 1, 4, 0.5, 0.1, 0.1, None) == ERR_NULL
+    assert f(arr, 1, rows, 2, 0, 7, 1, 4, 0.5, 0.1, 0.1, None) == ERR_PARAM       # gradient type
+    assert f(arr, 1, rows, 2, 0, 0, 1, 0, 0.5, 0.1, 0.1, None) == ERR_PARAM       # k
+    assert f(arr, 1, rows, 2, 0, 0, -1, 4, 0.5, 0.1, 0.1, None) == ERR_PARAM      # step
+    assert f(arr, 1, rows, 2, 0, 0, 1, 4, -0.5, 0.1, 0.1, None) == ERR_PARAM      # threshold
+    assert f(arr, 1, rows, 2, 0, 0, 1, 4, 0.5, float("inf"), 0.1, None) == ERR_PARAM
+    assert f((cdsgd_tensor * 1)(_tensor(L, w_local=A + 0x10004)), 1, rows, 2, 0, 0, 1, 4, 0.5, 0.1, 0.1, None) == ERR_ALIGN
+    assert f((cdsgd_tensor * 1)(_tensor(L, agg_full=None)), 1, rows, 2, 0, 0, 0, 4, 0.5, 0.1, 0.1, None) == ERR_NULL
+    # too many tensors
+    T = STATIC_MAX_TENSORS + 1
+    big = (cdsgd_tensor * T)(*[_tensor(L) for _ in range(T)])
+    bigrow = (ctypes.c_void_p * T)(*([A + 0x70000] * T))
+    bigrows = (ctypes.POINTER(ctypes.c_void_p) * 2)(ctypes.POINTER(ctypes.c_void_p)(),
+                                                    ctypes.cast(bigrow, ctypes.POINTER(ctypes.c_void_p)))
+    assert f(big, T, bigrows, 2, 0, 0, 1, 4, 0.5, 0.1, 0.1, None) == ERR_SIZE
+    # too many chunks: one tensor one chunk beyond the table (buffers spaced so that nothing overlaps)
+    n = STATIC_MAX_CHUNKS * STATIC_CHUNK_ELEMS + 1
+    t = cdsgd_tensor()
+    step_b = 1 << 34
+    t.w_global, t.w_local, t.residual, t.grad, t.packed_self, t.agg_full = (A + step_b * i for i in range(6))
+    t.n = n
+    farrow = (ctypes.c_void_p * 1)(A + step_b * 7)
+    farrows = (ctypes.POINTER(ctypes.c_void_p) * 2)(ctypes.POINTER(ctypes.c_void_p)(),
+                                                    ctypes.cast(farrow, ctypes.POINTER(ctypes.c_void_p)))
+    assert f((cdsgd_tensor * 1)(t), 1, farrows, 2, 0, 0, 1, 4, 0.5, 0.1, 0.1, None) == ERR_SIZE
+
+
 def test_aliasing_is_refused(L):
     """An output that overlaps an input (or another output) of the same tensor would make the
     result depend on the launch order; the host checks refuse it."""
