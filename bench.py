@@ -10,6 +10,13 @@ ResNet-50-shaped list and the 4 GiB flat bucket are reported in "extra".
 Prints ONE JSON line.  `value` is algorithmic GB/s = elements * (24 + N/4) bytes / step
 time with every input already resident in HBM; compressed steps only (correction steps,
 one in k, are timed separately and reported in "extra").
+
+Timing: after --warmup untimed steps, blocks of exactly --steps fused steps run back to back on
+the stream the kernels are launched on, with a HIP event between blocks and no host
+synchronisation inside the run, until at least 10 blocks and at least one second of GPU time
+have gone by.  `ms_per_step` is the MEDIAN block's time per step: a sustained figure.  The
+first and the last block (a GPU that has just been idle clocks higher than one under sustained
+load), the fastest and the slowest are in extra.headline.blocks.
 """
 import argparse
 import json
@@ -23,10 +30,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per k_fused_compressed launch from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this
-# file, scaled by the same counters' readings for a 1 GiB device copy (FETCH_SIZE x 2.0, WRITE_SIZE
-# x 1.0 on this GPU); summaries in profiles/k_fused_compressed_<workload>.md.
-MEASURED_TRAFFIC_BYTES = {"c4_vgg16": 3.8786e9, "c3_resnet50": 0.7170e9}
+# HBM bytes per k_fused_compressed launch.  NOT measured by this run: constants taken from earlier
+# rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this file, scaled by the same counters' readings
+# for a 1 GiB device copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 on this GPU); the summaries are
+# profiles/k_fused_compressed_<workload>.md.
+PROFILED_TRAFFIC_BYTES = {"c4_vgg16": 3.8786e9, "c3_resnet50": 0.7170e9}
+MIN_TIMED_SECONDS = 1.0     # sustained: the timed blocks of the headline cover at least this much GPU time
+MIN_BLOCKS = 10
 
 
 def _progress(msg):
@@ -44,7 +54,36 @@ def _compressed_steps(k, count, start=1):
     return out
 
 
-def time_workload(name, steps, warmup, want_correction=True, want_unfused=False, grad_dtype=None):
+def timed_blocks(run_block, steps, stream, min_seconds=MIN_TIMED_SECONDS, min_blocks=MIN_BLOCKS, max_blocks=2000):
+    """Blocks of `steps` launches back to back on `stream`, an event between blocks, one host
+    synchronisation at the end.  The number of blocks is chosen from one untimed block so that the
+    run covers min_seconds of GPU time and at least min_blocks blocks."""
+    import torch
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    run_block()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    est_ms = max(e0.elapsed_time(e1), 1e-3)
+    n = int(min(max_blocks, max(min_blocks, -(-min_seconds * 1e3 // est_ms))))
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+    ev[0].record(stream)
+    for b in range(n):
+        run_block()
+        ev[b + 1].record(stream)
+    torch.cuda.synchronize()
+    per = [ev[b].elapsed_time(ev[b + 1]) / steps for b in range(n)]      # ms per step, block by block
+    srt = sorted(per)
+    return {"blocks": n, "steps_per_block": steps, "timed_seconds": sum(per) * steps * 1e-3,
+            "median_ms_per_step": srt[n // 2] if n % 2 else 0.5 * (srt[n // 2 - 1] + srt[n // 2]),
+            "first_block_ms_per_step": per[0], "last_block_ms_per_step": per[-1],
+            "min_block_ms_per_step": srt[0], "max_block_ms_per_step": srt[-1],
+            "mean_ms_per_step": sum(per) / n}
+
+
+def time_workload(name, steps, warmup, want_correction=True, want_unfused=False, grad_dtype=None,
+                  min_seconds=MIN_TIMED_SECONDS):
     import torch
     from paper_2106_10796_amd import runner, synth
     cfg = synth.config(name)
@@ -60,54 +99,82 @@ def time_workload(name, steps, warmup, want_correction=True, want_unfused=False,
     torch.cuda.empty_cache()
     stream = torch.cuda.current_stream()
 
-    def run(step_numbers, fn):
+    def run(step_numbers, fn, min_seconds=0.0):
+        """ms per call of fn over the given step numbers, repeated back to back until min_seconds of
+        GPU time have gone by (one event pair around everything)."""
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        for s in step_numbers:
-            fn(s)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / len(step_numbers)   # ms per step
+        total_ms, calls = 0.0, 0
+        while True:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for s in step_numbers:
+                fn(s)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            total_ms += e0.elapsed_time(e1)
+            calls += len(step_numbers)
+            if total_ms >= min_seconds * 1e3:
+                return total_ms / calls
 
-    def per_step(step_numbers, fn):
-        """One event pair per step: the median is robust against a stray slow step."""
-        torch.cuda.synchronize()
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(step_numbers) + 1)]
-        ev[0].record(stream)
-        for i, s in enumerate(step_numbers):
-            fn(s)
-            ev[i + 1].record(stream)
-        torch.cuda.synchronize()
-        d = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(len(step_numbers)))
-        return d[len(d) // 2], d[0]
-
-    _progress("%s: timing %d fused steps" % (name, steps))
+    _progress("%s: timing blocks of %d fused steps" % (name, steps))
+    block_steps = _compressed_steps(cfg.k, steps)
     run(_compressed_steps(cfg.k, max(warmup, 1)), wl.fused_step)
-    ms = run(_compressed_steps(cfg.k, steps), wl.fused_step)
-    med, best = per_step(_compressed_steps(cfg.k, max(10, min(steps, 40))), wl.fused_step)
+    blocks = timed_blocks(lambda: [wl.fused_step(s) for s in block_steps], steps, stream, min_seconds)
+    ms = blocks["median_ms_per_step"]
     bpe = cfg.bytes_per_element - (4 - grad_bytes)        # 24 + N/4 with fp32 gradients, 22 + N/4 with 16-bit ones
     out = dict(workload=name, tensors=cfg.num_tensors, elements=cfg.elements, num_workers=cfg.num_workers,
                k=cfg.k, threshold=cfg.threshold, bytes_per_element=bpe,
-               ms_per_step=ms, median_ms_per_step=med, min_ms_per_step=best,
+               ms_per_step=ms, blocks=blocks,
                elems_per_s=cfg.elements / (ms * 1e-3),
                gbs=cfg.elements * bpe / (ms * 1e-3) / 1e9)
     out["frac_hbm_peak"] = out["gbs"] / HBM_PEAK_GBS
     if want_correction:
         run([0] * max(warmup, 1), wl.fused_step)
-        ms_c = run([0] * max(3, steps // 4), wl.fused_step)
+        ms_c = run([0] * max(3, steps // 4), wl.fused_step, min_seconds=0.3)
         out["correction_ms_per_step"] = ms_c
         out["correction_gbs"] = cfg.elements * (16.0 + grad_bytes) / (ms_c * 1e-3) / 1e9   # read W, g, agg; write W, Wloc
     if want_unfused:
         run(_compressed_steps(cfg.k, 1), wl.unfused_step)
-        ms_u = run(_compressed_steps(cfg.k, max(2, steps // 4)), wl.unfused_step)
+        ms_u = run(_compressed_steps(cfg.k, max(2, steps // 4)), wl.unfused_step, min_seconds=0.3)
         out["threecall_ms_per_step"] = ms_u
         # delta of the paper's model: the worker-side compression alone (quantise + pack, one flat call)
         from paper_2106_10796_amd import binding
         qp = lambda s: binding.cdsgd_quantize_pack(wl.grad, wl.residual, wl.packed_self, cfg.threshold)
         run([1], qp)
-        out["quantize_pack_ms"] = run([1] * max(3, steps // 4), qp)
+        out["quantize_pack_ms"] = run([1] * max(3, steps // 4), qp, min_seconds=0.2)
     return out, wl
+
+
+def stream_ceilings(wl, min_seconds=0.3):
+    """What plain streaming kernels reach on this GPU, on the same arenas and in the same run, for
+    comparison with the library's kernels: a fill (writes only), a sum (reads only), a copy
+    (1 read, 1 write) and an add (2 reads, 1 write).  These are torch's own elementwise kernels: harness, not product."""
+    import torch
+    stream = torch.cuda.current_stream()
+    n = wl.w_global.numel()
+    a, b, c = wl.w_global, wl.residual, wl.w_local
+    ops = {"fill_write_only": (lambda: c.fill_(1.0), 4.0 * n),
+           "sum_read_only": (lambda: torch.sum(a), 4.0 * n),
+           "copy_1r_1w": (lambda: c.copy_(a), 8.0 * n),
+           "add_2r_1w": (lambda: torch.add(a, b, out=c), 12.0 * n)}
+    out = {"elements": n, "note": "torch elementwise kernels on the workload's own fp32 arenas, >= %.1f s each, "
+                                  "after the headline (warm GPU)" % min_seconds}
+    for name, (fn, nbytes) in ops.items():
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        total_ms, calls = 0.0, 0
+        while total_ms < min_seconds * 1e3:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(20):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            total_ms += e0.elapsed_time(e1)
+            calls += 20
+        out[name + "_gbs"] = nbytes / (total_ms / calls * 1e-3) / 1e9
+    return out
 
 
 def time_small(name, steps=200):
@@ -163,26 +230,25 @@ def time_correction_sum(name, steps, warmup):
     stream = torch.cuda.current_stream()
     for _ in range(max(warmup, 1)):
         wl.fused_step(0)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(stream)
-    for _ in range(steps):
-        wl.fused_step(0)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / steps
+    blocks = timed_blocks(lambda: [wl.fused_step(0) for _ in range(steps)], steps, stream, min_seconds=0.5,
+                          min_blocks=5)
+    ms = blocks["median_ms_per_step"]
     bpe = 12.0 + 4.0 * cfg.num_workers
     wl.destroy()
-    return {"ms_per_step": ms, "bytes_per_element": bpe, "gbs": cfg.elements * bpe / (ms * 1e-3) / 1e9,
+    return {"ms_per_step": ms, "blocks": blocks, "bytes_per_element": bpe,
+            "gbs": cfg.elements * bpe / (ms * 1e-3) / 1e9,
             "frac_hbm_peak": cfg.elements * bpe / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
 
-def overlap_demo(name, iters=12):
+def overlap_demo(name, iters=16):
     """Overhead hiding on one GPU (Sec. 3.2.2, Fig. 5): the next forward pass only needs the local
-    weights.  Fused form: forward stand-in waits for the whole fused step.  Split form: stream L
+    weights.  Fused form: the forward stand-in waits for the whole fused step.  Split form: stream L
     runs cdsgd_step_local and then the forward stand-in, stream G runs cdsgd_step_global behind an
-    event; the next iteration's local update waits for G.  The stand-in is a compute-bound bf16
-    matrix product; both streams have the default priority."""
+    event; the next iteration's local update waits for G.  Both streams have the default priority.
+    cdsgd_step_global is run with one workgroup per chunk and with bounded grids
+    (cdsgd_plan_set_max_workgroups), which leave compute units to the stand-in.  Two stand-ins:
+    one bf16 matrix product that fills every compute unit, and a chain of small products that
+    does not (a forward pass bound by launch latency)."""
     import torch
     from paper_2106_10796_amd import runner, synth
     cfg = synth.config(name)
@@ -191,10 +257,6 @@ def overlap_demo(name, iters=12):
     wl.peer_residual = [None] * cfg.num_workers
     wl._scratch = None
     torch.cuda.empty_cache()
-    M = 8192
-    x = torch.randn(M, M, device="cuda", dtype=torch.bfloat16)
-    y = torch.randn(M, M, device="cuda", dtype=torch.bfloat16)
-    z = torch.empty(M, M, device="cuda", dtype=torch.bfloat16)
     main = torch.cuda.current_stream()
     side = torch.cuda.Stream()
     steps = _compressed_steps(cfg.k, iters)
@@ -202,59 +264,93 @@ def overlap_demo(name, iters=12):
     def timed(fn):
         fn()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(main)
-        fn()
-        e1.record(main)
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / iters
+        out = []
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(main)
+            fn()
+            e1.record(main)
+            torch.cuda.synchronize()
+            out.append(e0.elapsed_time(e1) / iters)
+        return sorted(out)[1]
 
     def only(fn):
         return lambda: [fn(s) for s in steps]
 
-    def fused_then_forward():
-        for s in steps:
-            wl.fused_step(s)
-            torch.mm(x, y, out=z)
+    def make_stand_in(kind):
+        if kind == "full_chip":
+            M = 8192
+            x = torch.randn(M, M, device="cuda", dtype=torch.bfloat16)
+            y = torch.randn(M, M, device="cuda", dtype=torch.bfloat16)
+            z = torch.empty(M, M, device="cuda", dtype=torch.bfloat16)
+            return "one bf16 %dx%dx%d matrix product" % (M, M, M), lambda: torch.mm(x, y, out=z)
+        M, reps = 1024, 48
+        x = torch.randn(M, M, device="cuda", dtype=torch.bfloat16)
+        y = torch.randn(M, M, device="cuda", dtype=torch.bfloat16)
+        z = torch.empty(M, M, device="cuda", dtype=torch.bfloat16)
+        return "%d bf16 %dx%dx%d matrix products in a row" % (reps, M, M, M), \
+            lambda: [torch.mm(x, y, out=z) for _ in range(reps)]
 
-    def split_serial():
-        for s in steps:
-            wl.plan.step_local(cfg.lr)
-            torch.mm(x, y, out=z)
-            wl.plan.step_global(s, cfg.k, cfg.threshold, cfg.lr)
-
-    def split_overlapped():
-        g_done = None
-        for s in steps:
-            if g_done is not None:
-                main.wait_event(g_done)            # next local update reads the new global weights
-            wl.plan.step_local(cfg.lr)
-            l_done = torch.cuda.Event()
-            l_done.record(main)
-            torch.mm(x, y, out=z)                  # forward stand-in, needs only w_local
-            with torch.cuda.stream(side):
-                side.wait_event(l_done)
-                wl.plan.step_global(s, cfg.k, cfg.threshold, cfg.lr)
-                g_done = torch.cuda.Event()
-                g_done.record(side)
-        main.wait_event(g_done)
-
-    out = {
-        "workload": name, "forward_stand_in": "bf16 %dx%dx%d matrix product" % (M, M, M),
-        "ms_fused_step": timed(only(wl.fused_step)),
-        "ms_step_local": timed(only(lambda s: wl.plan.step_local(cfg.lr))),
-        "ms_step_global": timed(only(lambda s: wl.plan.step_global(s, cfg.k, cfg.threshold, cfg.lr))),
-        "ms_forward_stand_in": timed(only(lambda s: torch.mm(x, y, out=z))),
-        "ms_iter_fused_then_forward": timed(fused_then_forward),
-        "ms_iter_split_one_stream": timed(split_serial),
-        "ms_iter_split_two_streams": timed(split_overlapped),
-    }
+    wl.plan.set_max_workgroups(0)
+    out = {"workload": name,
+           "ms_fused_step": timed(only(wl.fused_step)),
+           "ms_step_local": timed(only(lambda s: wl.plan.step_local(cfg.lr))),
+           "ms_step_global": timed(only(lambda s: wl.plan.step_global(s, cfg.k, cfg.threshold, cfg.lr))),
+           "stand_ins": {}}
     out["forward_can_start_after_ms"] = {"fused": out["ms_fused_step"], "split": out["ms_step_local"]}
+    limits = [0, 4096, 2048, 1024, 512, 256]
+    for kind in ("full_chip", "latency_bound"):
+        label, forward = make_stand_in(kind)
+
+        def fused_then_forward():
+            for s in steps:
+                wl.fused_step(s)
+                forward()
+
+        def split_serial():
+            for s in steps:
+                wl.plan.step_local(cfg.lr)
+                forward()
+                wl.plan.step_global(s, cfg.k, cfg.threshold, cfg.lr)
+
+        def split_overlapped():
+            g_done = None
+            for s in steps:
+                if g_done is not None:
+                    main.wait_event(g_done)            # next local update reads the new global weights
+                wl.plan.step_local(cfg.lr)
+                l_done = torch.cuda.Event()
+                l_done.record(main)
+                with torch.cuda.stream(side):
+                    side.wait_event(l_done)
+                    wl.plan.step_global(s, cfg.k, cfg.threshold, cfg.lr)
+                    g_done = torch.cuda.Event()
+                    g_done.record(side)
+                forward()                              # forward stand-in, needs only w_local
+            main.wait_event(g_done)
+
+        r = {"forward_stand_in": label, "ms_forward_stand_in": timed(only(lambda s: forward()))}
+        r["ms_iter_fused_then_forward"] = timed(fused_then_forward)
+        r["ms_iter_split_one_stream"] = timed(split_serial)
+        r["ms_iter_ideal_overlap"] = out["ms_step_local"] + max(r["ms_forward_stand_in"], out["ms_step_global"])
+        two = {}
+        for lim in limits:
+            wl.plan.set_max_workgroups(lim)
+            two["per_chunk" if lim == 0 else str(lim)] = {
+                "ms_step_global_alone": timed(only(lambda s: wl.plan.step_global(s, cfg.k, cfg.threshold, cfg.lr))),
+                "ms_iter_split_two_streams": timed(split_overlapped)}
+        wl.plan.set_max_workgroups(0)
+        r["two_streams_by_workgroup_limit_of_step_global"] = two
+        best = min(two, key=lambda q: two[q]["ms_iter_split_two_streams"])
+        r["best_two_streams"] = {"workgroup_limit": best, "ms_iter": two[best]["ms_iter_split_two_streams"],
+                                 "vs_fused_then_forward": two[best]["ms_iter_split_two_streams"]
+                                 / r["ms_iter_fused_then_forward"]}
+        out["stand_ins"][kind] = r
     wl.destroy()
     return out
 
 
-def cpu_baseline(wl, target_seconds=40.0):
+def cpu_baseline(wl, target_seconds=20.0):
     """The oracle as it stands, timed on this host: worker 0's fused-equivalent work
     (quantise + pack own gradient, decode-and-sum N streams, both updates) on a bounded
     sample of the same workload, split over the host cores by element range (the work is
@@ -337,6 +433,9 @@ def main():
     ap.add_argument("--workload", default="c4_vgg16")
     ap.add_argument("--no-extra", action="store_true", help="skip the ResNet-50 and 4 GiB workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only-correction-sum", action="store_true",
+                    help="time only the correction pass that sums the N gradients in the kernel (for profiling "
+                         "k_fused_full<true, ...> on its own) and print its figures instead of the benchmark line")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain device copy of known size (1 GiB read + 1 GiB written, 3 times): "
                          "under rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings give the counters' scale")
@@ -362,8 +461,14 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
+    if args.only_correction_sum:
+        r = time_correction_sum(args.workload, args.steps, args.warmup)
+        r["workload"] = args.workload
+        print(json.dumps(r))
+        return 0
     head, wl = time_workload(args.workload, args.steps, args.warmup, want_correction=True,
                              want_unfused=not args.no_extra)
+    ceilings = None if args.no_extra else stream_ceilings(wl)
     cpu = None
     if not args.no_cpu_baseline:
         _progress("cpu baseline (oracle on the host cores)")
@@ -373,6 +478,7 @@ def main():
     torch.cuda.empty_cache()
     extra = {"headline": head}
     if not args.no_extra:
+        extra["stream_ceilings"] = ceilings
         _progress("extras: correction with kernel sum, overlap, small workloads, bf16 gradients, other workloads")
         extra["correction_with_kernel_sum_" + args.workload] = time_correction_sum(
             args.workload, max(3, args.steps // 4), max(1, args.warmup // 2))
@@ -382,7 +488,7 @@ def main():
         for name in ("c1_single", "c2_resnet20"):
             extra[name] = time_small(name)
         r, w = time_workload(args.workload, max(5, args.steps // 2), max(2, args.warmup // 2),
-                             want_correction=False, grad_dtype=torch.bfloat16)
+                             want_correction=False, grad_dtype=torch.bfloat16, min_seconds=0.5)
         w.destroy()
         del w
         torch.cuda.empty_cache()
@@ -403,7 +509,7 @@ def main():
             if name == args.workload:
                 continue
             r, w = time_workload(name, max(5, args.steps // 2), max(2, args.warmup // 2),
-                                 want_correction=(name != "c5_flat4g"))
+                                 want_correction=(name != "c5_flat4g"), min_seconds=0.5)
             w.destroy()
             del w
             torch.cuda.empty_cache()
@@ -415,6 +521,9 @@ def main():
         "value": head["gbs"], "unit": "GB/s",
         "elems_per_s": head["elems_per_s"],
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "timing": "median of %d back-to-back blocks of %d steps (%.2f s of GPU time); first block %.4f, last block "
+                  "%.4f ms/step" % (head["blocks"]["blocks"], args.steps, head["blocks"]["timed_seconds"],
+                                    head["blocks"]["first_block_ms_per_step"], head["blocks"]["last_block_ms_per_step"]),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: VGG-16-shaped layer list" % head["workload"] if head["workload"] == "c4_vgg16"
@@ -426,7 +535,9 @@ def main():
                      "achieved": bytes_per_launch / (head["ms_per_step"] * 1e-3) / 1e9,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": bytes_per_launch / (head["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(head["workload"])},
+                     "traffic": PROFILED_TRAFFIC_BYTES.get(head["workload"]),
+                     "traffic_source": "constant from profiles/k_fused_compressed_%s.md (rocprofv3 --pmc FETCH_SIZE / "
+                                       "WRITE_SIZE), not measured by this run" % head["workload"]},
         "cpu_baseline": cpu,
         "extra": extra,
         "paper_context": "end-to-end time 30% below 2-bit compression on a 16-GPU MXNet cluster at 56 Gbps "

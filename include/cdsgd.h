@@ -211,6 +211,17 @@ int cdsgd_step_global(cdsgd_plan *plan, long step, int k, float threshold, float
                       void *hip_stream);
 
 /*
+ * Bound the number of workgroups that the passes of this plan launch (Sec. 3.2.2: the rest of
+ * the step should not stand in the way of the next iteration's computation).  By default a
+ * pass launches one workgroup per 4096-element chunk of the layer list and fills the GPU; with
+ * a limit it launches at most max_workgroups workgroups, each walking several chunks, so that
+ * a pass enqueued on a second stream leaves compute units to kernels that run beside it.  The
+ * results are bit for bit the same for every limit.  0 removes the limit; negative values are
+ * CDSGD_ERR_PARAM.  Host-side setting only: it applies to passes enqueued after the call.
+ */
+int cdsgd_plan_set_max_workgroups(cdsgd_plan *plan, int max_workgroups);
+
+/*
  * Let correction and warm-up passes sum the workers' 32-bit gradients themselves
  * (Alg. 1, else-branch and WARMUP; the sum of eq. 1) instead of reading agg_full:
  * one launch then reads W and the N gradients and writes W and W_loc.

@@ -31,6 +31,8 @@
  *   oracle_trainer_step  Alg. 1 as a whole: WARMUP for i = 0..n, then FormalTraining
  *   oracle_cost_model    eq. 2, 4, 5, 6, 7 (iteration times); the savings are the
  *                        differences T_loc - T_cd and T_bit - T_cd that Sec. 3.3 defines
+ *   oracle_sparse_encode/decode   no passage: a wire format of this build for the same
+ *                        packed words (Sec. 7 only names sparsification as future work)
  *
  * Every function here is pinned by tests/test_oracle_pins.py (hand-unrolled
  * recurrence, closed forms, invariants, brute force on tiny inputs).  The
@@ -223,6 +225,54 @@ int oracle_trainer_step(float *w_global, float *w_local, float *const *residual,
                        iter - warmup_n - 1, k, t, lr_local, lr_global)
                ? 1
                : 2;
+}
+
+/* Sparse form of a packed stream -- THIS BUILD'S OWN FORMAT, not the paper's: Sec. 7 names a
+ * combination with sparsification as future work and defines nothing, so these two functions
+ * follow the definition in the library's header and are pinned only to that definition (a
+ * hand-worked fixture, round trips on every tail, densities 0 and 1).  The method itself is
+ * untouched: a decoded sparse stream is the packed stream again, word for word.
+ *
+ * A stream of nw = ceil(n / 16) words is cut into segments of 256 words (4096 elements).
+ * Segment s occupies words [264 s, 264 s + 264) of the sparse buffer: first 8 bitmap words
+ * (bit b of bitmap word m set iff packed word 256 s + 32 m + b exists and is non-zero), then
+ * the non-zero words of the segment in index order; the slots after them are left as they are.
+ * seg_words[s] receives 8 + (number of non-zero words): what a sender would put on the wire. */
+void oracle_sparse_encode(const uint32_t *word, size_t n, uint32_t *sparse, uint32_t *seg_words)
+{
+    size_t nw = (n + 15) / 16;
+    size_t nseg = (nw + 255) / 256;
+    for (size_t s = 0; s < nseg; ++s) {
+        uint32_t *seg = sparse + 264 * s;
+        uint32_t count = 0;
+        for (int m = 0; m < 8; ++m) seg[m] = 0u;
+        for (size_t i = 0; i < 256; ++i) {
+            size_t w = 256 * s + i;
+            if (w < nw && word[w] != 0u) {
+                seg[i / 32] |= 1u << (i % 32);
+                seg[8 + count] = word[w];
+                ++count;
+            }
+        }
+        if (seg_words) seg_words[s] = 8u + count;
+    }
+}
+
+/* Inverse of oracle_sparse_encode: rebuilds the nw packed words. */
+void oracle_sparse_decode(const uint32_t *sparse, size_t n, uint32_t *word)
+{
+    size_t nw = (n + 15) / 16;
+    for (size_t w = 0; w < nw; ++w) {
+        const uint32_t *seg = sparse + 264 * (w / 256);
+        size_t i = w % 256;
+        if ((seg[i / 32] >> (i % 32)) & 1u) {
+            uint32_t before = 0; /* set bits below bit i of the segment's bitmap */
+            for (size_t b = 0; b < i; ++b) before += (seg[b / 32] >> (b % 32)) & 1u;
+            word[w] = seg[8 + before];
+        } else {
+            word[w] = 0u;
+        }
+    }
 }
 
 /* The paper's time model, from the definitions only (in double: these are

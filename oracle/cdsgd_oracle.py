@@ -53,6 +53,10 @@ def lib():
                                           ctypes.POINTER(_u32p), _f32p, _u8p, ctypes.c_size_t, ctypes.c_int,
                                           ctypes.c_int, ctypes.c_long, ctypes.c_long, ctypes.c_int,
                                           ctypes.c_float, ctypes.c_float, ctypes.c_float]
+        L.oracle_sparse_encode.restype = None
+        L.oracle_sparse_encode.argtypes = [_u32p, ctypes.c_size_t, _u32p, _u32p]
+        L.oracle_sparse_decode.restype = None
+        L.oracle_sparse_decode.argtypes = [_u32p, ctypes.c_size_t, _u32p]
         L.oracle_cost_model.restype = None
         L.oracle_cost_model.argtypes = [ctypes.c_double] * 4 + [ctypes.c_int, ctypes.c_long,
                                                                 ctypes.POINTER(ctypes.c_double)]
@@ -141,6 +145,31 @@ def update(w_global, w_local, grad_local, agg, lr_local, lr_global, num_workers)
             _chk(a, np.float32, n)
     lib().oracle_update(_p(w_global, _f32p), _p(w_local, _f32p), _p(grad_local, _f32p), _p(agg, _f32p),
                         n, float(lr_local), float(lr_global), int(num_workers))
+
+
+def sparse_segments(n: int) -> int:
+    return (packed_words(n) + 255) // 256
+
+
+def sparse_words(n: int) -> int:
+    """Capacity of a sparse buffer for n elements: 264 words per segment of 256 packed words."""
+    return 264 * sparse_segments(n)
+
+
+def sparse_encode(word, n, fill=0):
+    """(sparse buffer, words per segment on the wire).  Slots the format leaves alone keep `fill`."""
+    _chk(word, np.uint32, packed_words(n))
+    sparse = np.full(sparse_words(n), fill, np.uint32)
+    seg = np.zeros(sparse_segments(n), np.uint32)
+    lib().oracle_sparse_encode(_p(word, _u32p), n, _p(sparse, _u32p), _p(seg, _u32p))
+    return sparse, seg
+
+
+def sparse_decode(sparse, n):
+    _chk(sparse, np.uint32, sparse_words(n))
+    word = np.empty(packed_words(n), np.uint32)
+    lib().oracle_sparse_decode(_p(sparse, _u32p), n, _p(word, _u32p))
+    return word
 
 
 def cost_model(tau, phi, psi, delta, k, i):

@@ -84,6 +84,8 @@ def lib():
                                               i, i, i, ctypes.POINTER(vp)]
         L.cdsgd_plan_set_thresholds.restype = i
         L.cdsgd_plan_set_thresholds.argtypes = [vp, ctypes.POINTER(f)]
+        L.cdsgd_plan_set_max_workgroups.restype = i
+        L.cdsgd_plan_set_max_workgroups.argtypes = [vp, i]
         L.cdsgd_step_local.restype = i
         L.cdsgd_step_local.argtypes = [vp, f, vp]
         L.cdsgd_step_global.restype = i
@@ -270,6 +272,11 @@ class Plan:
             arr = (ctypes.c_float * len(thresholds))(*[float(x) for x in thresholds])
             st = lib().cdsgd_plan_set_thresholds(self._handle, arr)
         _check(st, "cdsgd_plan_set_thresholds")
+
+    def set_max_workgroups(self, max_workgroups):
+        """At most this many workgroups per pass (0: one per chunk); cdsgd_plan_set_max_workgroups."""
+        _check(lib().cdsgd_plan_set_max_workgroups(self._handle, int(max_workgroups)),
+               "cdsgd_plan_set_max_workgroups")
 
     def step_local(self, lr_local):
         st = lib().cdsgd_step_local(self._handle, float(lr_local), _stream())

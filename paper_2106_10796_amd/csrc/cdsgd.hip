@@ -4,16 +4,21 @@
 // consecutive fp32 elements = one 128-bit load/store per buffer = one byte of
 // the packed stream (four 2-bit codes; element e of a tensor is bits
 // [2(e%4)+1 : 2(e%4)] of packed byte e/4, which is the little-endian view of
-// the 32-bit-word layout in cdsgd.h).  A workgroup of kBlock lanes owns a
-// "chunk" of kQpl * kBlock consecutive quads; lane `tid` takes quads
-// j*kBlock + tid, so every wave instruction touches one contiguous 1 KiB
-// (fp32 buffers) or 64 B (packed streams) span: all traffic is fully
-// coalesced and no cross-lane exchange is needed to build or to read the
-// packed words.
+// the 32-bit-word layout in cdsgd.h).  A tensor is cut into "chunks" of 1024
+// quads (4096 elements, 1 KiB of a packed stream); the chunk table of a plan
+// lists (tensor, chunk) pairs, and only a tensor's last chunk can be ragged.
+//   * The kernels over a layer list work on "pieces" of a chunk, one quad per
+//     lane: 256-lane workgroups for the compressed pass (the peers' codes
+//     come in through LDS, 128 bits per lane and 16 peers per instruction),
+//     single waves for the passes on 32-bit gradients.
+//   * The single-tensor kernels give a chunk to a workgroup of kBlock lanes,
+//     lane `tid` taking quads j*kBlock + tid.
+// Either way every wave instruction on an fp32 buffer touches one contiguous
+// 1 KiB span: all traffic is fully coalesced.
 //
-// The path is elementwise and HBM-bound: no LDS tiles, no MFMA.  Each of
-// grad / residual / w_global is read once and each of residual / w_global /
-// w_local is written once per step.
+// The path is elementwise and HBM-bound: no MFMA.  Each of grad / residual /
+// w_global is read once and each of residual / w_global / w_local is written
+// once per step.
 
 #include <hip/hip_runtime.h>
 
@@ -49,11 +54,17 @@
 #ifndef CDSGD_NT_CODES
 #define CDSGD_NT_CODES 0
 #endif
-#ifndef CDSGD_FULL_BATCH
-#define CDSGD_FULL_BATCH 8
+#ifndef CDSGD_XCD_FULL
+#define CDSGD_XCD_FULL 0
 #endif
-#ifndef CDSGD_XCD_REMAP
-#define CDSGD_XCD_REMAP 0
+#ifndef CDSGD_PIECE_WAVES
+#define CDSGD_PIECE_WAVES 4
+#endif
+#ifndef CDSGD_XCD_PIECES
+#define CDSGD_XCD_PIECES 1
+#endif
+#ifndef CDSGD_FULL_BLOCK
+#define CDSGD_FULL_BLOCK 64
 #endif
 #ifndef CDSGD_PEER_BATCH
 #define CDSGD_PEER_BATCH 4
@@ -349,19 +360,14 @@ struct ChunkRef {
     unsigned chunk;   // chunk number inside that tensor
 };
 
-// Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b % 8).
-// With the remap, XCD x walks the x-th contiguous eighth of the chunk list instead of
-// every eighth chunk.
-__device__ __forceinline__ unsigned chunk_slot()
-{
-#if CDSGD_XCD_REMAP
-    const unsigned b = blockIdx.x;
-    const unsigned per = gridDim.x >> 3;
-    return b < (per << 3) ? (b & 7u) * per + (b >> 3) : b;
-#else
-    return blockIdx.x;
-#endif
-}
+// Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b % 8), so
+// consecutive chunks run on different XCDs; a streaming pass has no reuse for an XCD's L2 to
+// exploit, and giving each XCD a contiguous eighth of the chunk list measured no better.
+//
+// Every kernel over a layer list walks the chunk table from its workgroup number in steps of
+// the grid size.  Normally the grid has one workgroup per chunk and the loop runs once; a plan
+// with a workgroup limit (cdsgd_plan_set_max_workgroups) launches fewer workgroups, which then
+// take several chunks each and leave compute units free for other kernels.
 
 // ---------------------------------------------------------------------------
 // kernels
@@ -501,112 +507,206 @@ __global__ __launch_bounds__(CDSGD_BLOCK) void k_update(float *__restrict__ wg, 
     else update_chunk<true, LOCAL, GLOBAL>(wg, wl, grad, agg, ext.tail_elems, lr_local, scale);
 }
 
-// Fused compressed step (a1-a6) for one chunk of one tensor.
-template <bool G, bool POW2, bool WRITE_LOCAL, int GT>
-__device__ __forceinline__ void fused_chunk(const TensorDesc &d, const uint8_t *const *__restrict__ peers,
-                                            int num_peers, int self, size_t quad0, unsigned rem_elems,
-                                            unsigned rem_bytes, float t, float lr_local, float scale,
-                                            float bias_t)
+// Piece-granular kernels: which piece workgroup b takes.  Workgroup b runs on XCD b % 8.  Within
+// a block of 8 chunks' worth of workgroups, XCD k takes every piece of chunk k, so that the two
+// halves of a 128-byte line of a peer's codes, and the pieces' reads of the chunk's table
+// entries, meet in one L2 (measured on the ResNet-50-shaped list: 6.1 -> 6.8 TB/s).  The last,
+// incomplete block keeps the plain order.  A bijection on [0, num_pieces) for any grid size.
+template <bool XCD>
+__device__ __forceinline__ unsigned long long piece_of_workgroup(unsigned long long b, unsigned per_chunk,
+                                                                 unsigned long long num_pieces)
 {
-    const unsigned tid = threadIdx.x;
+    if (!XCD) return b;
+#if CDSGD_XCD_PIECES
+    const unsigned long long group = 8ull * per_chunk;
+    const unsigned long long blk = b / group, within = b % group;
+    if ((blk + 1) * group <= num_pieces) return (blk * 8 + within % 8) * per_chunk + within / 8;
+#endif
+    return b;
+}
+
+// ---------------------------------------------------------------------------
+// Fused compressed step (a1-a6), one workgroup per piece of a chunk
+// ---------------------------------------------------------------------------
+// A piece is 256 quads (1024 elements): 4 KiB of every fp32 stream and 256 bytes, two whole
+// 128-byte lines, of every packed stream.  Its workgroup has 256 lanes (four waves), one quad
+// and therefore one packed byte per lane.
+//
+// The peers' codes of a piece are fetched with ONE 128-bit load instruction per 16 peers: lane L
+// takes bytes [16 (L % 16), +16) of peer L / 16, the workgroup writes them to LDS as
+// [peer][byte], and every lane then reads its own byte of each peer back (LDS staging instead
+// of one byte-wide global load per peer and lane).  No load of a peer's codes depends on
+// another, so a workgroup's life is one round trip to memory however many workers there are,
+// and the memory system sees the packed streams as whole lines.
+//
+// Measured on the VGG-16-shaped list (N = 16, count form): 6.3-6.4 TB/s, where 512-lane
+// workgroups that took a whole chunk, two quads per lane and a byte load per peer, reached
+// 6.0 TB/s; with one wave per piece (64 bytes per peer, half a line) 5.8-6.0 TB/s.
+constexpr unsigned kPieceWaves = CDSGD_PIECE_WAVES;
+constexpr unsigned kPieceQuads = 64 * kPieceWaves;  // lanes per workgroup, one quad each
+constexpr unsigned kCompPiecesPerChunk = kChunkQuads / kPieceQuads;
+static_assert(kChunkQuads % kPieceQuads == 0, "pieces tile a chunk");
+constexpr unsigned kPeerSlots = 64;  // LDS rows: peers rounded up to a multiple of 16 (63 peers at most)
+static_assert(CDSGD_MAX_WORKERS - 1 <= kPeerSlots, "an LDS row for every peer");
+
+typedef unsigned u4 __attribute__((ext_vector_type(4)));
+
+// values of the four codes of a byte, as 2-bit two's-complement fields (01 -> +1, 10 -> -1, else 0)
+__device__ __forceinline__ unsigned signed_fields(unsigned w)
+{
+    const unsigned x = w & 0x55555555u;
+    const unsigned y = (w >> 1) & 0x55555555u;
+    return (x ^ y) | ((y & ~x) << 1);
+}
+
+template <bool G, bool POW2, bool WRITE_LOCAL, int GT>
+__device__ __forceinline__ void fused_piece(const TensorDesc &d, const uint8_t *const *__restrict__ peers,
+                                            int num_peers, int self, size_t quad0, unsigned piece,
+                                            unsigned rem_elems, unsigned rem_bytes, float t, float lr_local,
+                                            float scale, uint8_t *lds)
+{
+    const unsigned lane = threadIdx.x;
+    const unsigned qi = piece * kPieceQuads + lane;  // quad of the chunk = byte of the chunk's packed streams
     const void *__restrict__ grad = grad_at<GT>(d.grad, quad0);
     float *__restrict__ resid = d.residual + 4 * quad0;
     float *__restrict__ wg = d.w_global + 4 * quad0;
     float *__restrict__ wl = d.w_local + 4 * quad0;
     uint8_t *__restrict__ pself = d.packed_self + quad0;
+    const int cnt = quad_count<G>(rem_elems, qi);
 
-    f4 g[kQpl], r[kQpl], w[kQpl], agg[kQpl], sent[kQpl];
-    int cnt[kQpl];
+    // the peers' bytes of this piece: 16 peers per load instruction
+    constexpr unsigned kParts = kPieceQuads / 16;        // 16-byte parts of a peer's bytes of one piece
+    const unsigned part = lane % kParts;                 // which of them this lane fetches
+    const unsigned first = piece * kPieceQuads + 16u * part;  // its first byte within the chunk
+    const int groups = (num_peers + 15) >> 4;
+    u4 cw[kPeerSlots / 16];
 #pragma unroll
-    for (unsigned j = 0; j < kQpl; ++j) {
-        const unsigned qi = j * kBlock + tid;
-        cnt[j] = quad_count<G>(rem_elems, qi);
-        g[j] = ldgrad<G, GT>(grad, qi, cnt[j]);
-        r[j] = ld4g<G>(resid, qi, cnt[j]);
-    }
+    for (int gI = 0; gI < (int)(kPeerSlots / 16); ++gI) {
+        cw[gI] = u4{0u, 0u, 0u, 0u};
+        const int p = 16 * gI + (int)(lane / kParts);
+        if (gI < groups && p < num_peers) {
+            const uint8_t *src = peers[p] + quad0 + first;
+            if (!G || first + 16u <= rem_bytes) {
+                typedef unsigned u4a __attribute__((ext_vector_type(4), aligned(4)));
+                cw[gI] = *reinterpret_cast<const u4a *>(src);
+            } else {
+                // ragged end of the stream (a whole number of 32-bit words): word by word
 #pragma unroll
-    for (unsigned j = 0; j < kQpl; ++j) {
-        const unsigned qi = j * kBlock + tid;
-        w[j] = ld4g<G>(wg, qi, cnt[j]);
-        agg[j] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+                for (unsigned i = 0; i < 4; ++i)
+                    if (first + 4u * i < rem_bytes) cw[gI][i] = *reinterpret_cast<const unsigned *>(src + 4u * i);
+            }
+        }
     }
+
+    f4 g = ldgrad<G, GT>(grad, qi, cnt);
+    f4 r = ld4g<G>(resid, qi, cnt);
+    const f4 w = ld4g<G>(wg, qi, cnt);
 
     // own codes: quantise, keep the residual, write what would be pushed
-    unsigned own = 0;
-#pragma unroll
-    for (unsigned j = 0; j < kQpl; ++j) {
-        const unsigned qi = j * kBlock + tid;
-        const unsigned b = quantize_quad(g[j], r[j], t, sent[j]);
-        st4g<G>(resid, qi, cnt[j], r[j]);
-        if (!G || qi < rem_bytes) pself[qi] = (uint8_t)b;
-        own |= b << (8 * j);
-    }
+    f4 sent;
+    const unsigned own = quantize_quad(g, r, t, sent);
+    st4g<G>(resid, qi, cnt, r);
+    if (!G || qi < rem_bytes) pself[qi] = (uint8_t)own;
 
-    // aggregate: workers 0..self-1, own codes, workers self+1..N-1
-    unsigned acc[4] = {0u, 0u, 0u, 0u};
-    sum_streams<G, POW2>(agg, acc, peers, 0, self, quad0, tid, rem_bytes, t);
-    if (POW2) {
-        count_codes(acc, own);
+    // stage the peers' bytes: row p of the LDS block holds peer p's bytes of this piece
+#pragma unroll
+    for (int gI = 0; gI < (int)(kPeerSlots / 16); ++gI)
+        if (gI < groups) *reinterpret_cast<u4 *>(lds + (16u * gI + lane / kParts) * kPieceQuads + 16u * part) = cw[gI];
+    if (kPieceWaves == 1) {
+        // one wave per workgroup: a wave-level release / acquire pair orders its LDS writes before its reads
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     } else {
-#pragma unroll
-        for (unsigned j = 0; j < kQpl; ++j) agg[j] = agg[j] + sent[j];
+        __syncthreads();
     }
-    sum_streams<G, POW2>(agg, acc, peers, self, num_peers, quad0, tid, rem_bytes, t);
-    if (POW2) counts_to_sum(agg, acc, t, bias_t);
 
-    // eq. 11 and eq. 10 from the same loaded weight
-#pragma unroll
-    for (unsigned j = 0; j < kQpl; ++j) {
-        const unsigned qi = j * kBlock + tid;
-        f4 vl, vg;
+    f4 agg = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (POW2) {
+        // count form: four workers' bytes side by side in one register; field k of acc[c] collects
+        // 2 + value for element c of the workers in byte position k
+        unsigned acc[4] = {0u, 0u, 0u, 0u};
+        auto add4 = [&](unsigned w4) {
+            const unsigned z = ((w4 & 0x55555555u) | 0xAAAAAAAAu) - ((w4 >> 1) & 0x55555555u);
+            acc[0] += z & 0x03030303u;
+            acc[1] += (z >> 2) & 0x03030303u;
+            acc[2] += (z >> 4) & 0x03030303u;
+            acc[3] += (z >> 6) & 0x03030303u;
+        };
+        add4(own);  // the own byte and three empty positions
+        const int words = (num_peers + 3) >> 2;
+        for (int q = 0; q < words; ++q) {
+            const uint8_t *row = lds + (4u * q) * kPieceQuads + lane;
+            const unsigned w4 = (unsigned)row[0] | ((unsigned)row[kPieceQuads] << 8) |
+                                ((unsigned)row[2 * kPieceQuads] << 16) | ((unsigned)row[3 * kPieceQuads] << 24);
+            add4(w4);
+        }
+        // every position added 2 whether a worker stood there or not
+        const float bias_t = -(2.0f * (float)(4 * words + 4)) * t;
 #pragma unroll
         for (unsigned c = 0; c < 4; ++c) {
-            vl[c] = __builtin_fmaf(-lr_local, g[j][c], w[j][c]);
-            vg[c] = __builtin_fmaf(-scale, agg[j][c], w[j][c]);
+            const unsigned a = acc[c];
+            const unsigned sum = (a & 0xFFu) + ((a >> 8) & 0xFFu) + ((a >> 16) & 0xFFu) + (a >> 24);
+            agg[c] = __builtin_fmaf((float)sum, t, bias_t);
         }
-        if (WRITE_LOCAL) st4g<G>(wl, qi, cnt[j], vl);
-        st4g<G>(wg, qi, cnt[j], vg);
+    } else {
+        // literal chain: one rounded add per worker and element, worker order, own codes at `self`
+        auto chain = [&](unsigned b) {
+            const unsigned sf = signed_fields(b);
+#pragma unroll
+            for (unsigned c = 0; c < 4; ++c) {
+                const int m = ((int)(sf << (30u - 2u * c))) >> 30;
+                agg[c] = __builtin_fmaf((float)m, t, agg[c]);
+            }
+        };
+        for (int p = 0; p < self; ++p) chain(lds[(unsigned)p * kPieceQuads + lane]);
+        agg = agg + sent;
+        for (int p = self; p < num_peers; ++p) chain(lds[(unsigned)p * kPieceQuads + lane]);
+    }
+
+    // eq. 11 and eq. 10 from the same loaded weight
+    f4 vl, vg;
+#pragma unroll
+    for (unsigned c = 0; c < 4; ++c) {
+        vl[c] = __builtin_fmaf(-lr_local, g[c], w[c]);
+        vg[c] = __builtin_fmaf(-scale, agg[c], w[c]);
+    }
+    if (WRITE_LOCAL) st4g<G>(wl, qi, cnt, vl);
+    st4g<G>(wg, qi, cnt, vg);
+    // the next piece of this workgroup overwrites the LDS block: keep its writes behind these reads
+    if (kPieceWaves == 1) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    } else {
+        __syncthreads();
     }
 }
 
-// peers: [num_tensors][num_peers] pointers, this worker's own row left out.
-// WRITE_LOCAL = false leaves eq. 11 to a separate, earlier launch (k_plan_local).
 template <bool POW2, bool WRITE_LOCAL, int GT>
-__global__ __launch_bounds__(CDSGD_BLOCK) void k_fused_compressed(const TensorDesc *__restrict__ tensors,
-                                                                  const ChunkRef *__restrict__ chunks,
-                                                                  const uint8_t *const *__restrict__ peers,
-                                                                  int num_peers, int self, float t_call,
-                                                                  float lr_local, float scale)
+__global__ __launch_bounds__(64 * CDSGD_PIECE_WAVES) void k_fused_compressed(const TensorDesc *__restrict__ tensors,
+                                                                const ChunkRef *__restrict__ chunks,
+                                                                unsigned long long num_pieces,
+                                                                const uint8_t *const *__restrict__ peers,
+                                                                int num_peers, int self, float t_call,
+                                                                float lr_local, float scale)
 {
-    const ChunkRef cr = chunks[chunk_slot()];
-    const TensorDesc d = tensors[cr.tensor];
-    const size_t quad0 = (size_t)cr.chunk * kChunkQuads;
-    const uint8_t *const *tp = peers + (size_t)cr.tensor * (size_t)num_peers;
-    const float t = d.threshold > 0.0f ? d.threshold : t_call;
-    const float bias_t = -(2.0f * (float)(num_peers + 1)) * t;  // exact for the count form (t = 2^e)
-    if (cr.chunk < d.ext.full_chunks)
-        fused_chunk<false, POW2, WRITE_LOCAL, GT>(d, tp, num_peers, self, quad0, kChunkElems, kChunkQuads, t, lr_local,
-                                              scale, bias_t);
-    else
-        fused_chunk<true, POW2, WRITE_LOCAL, GT>(d, tp, num_peers, self, quad0, d.ext.tail_elems, d.ext.tail_bytes, t, lr_local,
-                                scale, bias_t);
-}
-
-// eq. 11 alone over the layer list: w_local = W - lr_local * g (reads W, g; writes w_local).
-template <int GT>
-__global__ __launch_bounds__(CDSGD_BLOCK) void k_plan_local(const TensorDesc *__restrict__ tensors,
-                                                            const ChunkRef *__restrict__ chunks, float lr_local)
-{
-    const ChunkRef cr = chunks[chunk_slot()];
-    const TensorDesc d = tensors[cr.tensor];
-    const size_t quad0 = (size_t)cr.chunk * kChunkQuads;
-    float *wg = d.w_global + 4 * quad0;
-    float *wl = d.w_local + 4 * quad0;
-    const void *grad = grad_at<GT>(d.grad, quad0);
-    if (cr.chunk < d.ext.full_chunks)
-        update_chunk<false, true, false, GT>(wg, wl, grad, nullptr, kChunkElems, lr_local, 0.0f);
-    else
-        update_chunk<true, true, false, GT>(wg, wl, grad, nullptr, d.ext.tail_elems, lr_local, 0.0f);
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kPeerSlots * kPieceQuads];
+    for (unsigned long long b = blockIdx.x; b < num_pieces; b += gridDim.x) {
+        const unsigned long long x = piece_of_workgroup<true>(b, kCompPiecesPerChunk, num_pieces);
+        const ChunkRef cr = chunks[x / kCompPiecesPerChunk];
+        const TensorDesc d = tensors[cr.tensor];
+        const size_t quad0 = (size_t)cr.chunk * kChunkQuads;
+        const unsigned piece = (unsigned)(x % kCompPiecesPerChunk);
+        const uint8_t *const *tp = peers + (size_t)cr.tensor * (size_t)num_peers;
+        const float t = d.threshold > 0.0f ? d.threshold : t_call;
+        if (cr.chunk < d.ext.full_chunks) {
+            fused_piece<false, POW2, WRITE_LOCAL, GT>(d, tp, num_peers, self, quad0, piece, kChunkElems, kChunkQuads, t,
+                                                      lr_local, scale, lds);
+        } else if (piece * kPieceQuads * 4u < d.ext.tail_elems || piece * kPieceQuads < d.ext.tail_bytes) {
+            fused_piece<true, POW2, WRITE_LOCAL, GT>(d, tp, num_peers, self, quad0, piece, d.ext.tail_elems,
+                                                     d.ext.tail_bytes, t, lr_local, scale, lds);
+        }
+    }
 }
 
 // Passes that use the workers' 32-bit gradients (Alg. 1: WARMUP passes and the
@@ -615,88 +715,86 @@ __global__ __launch_bounds__(CDSGD_BLOCK) void k_plan_local(const TensorDesc *__
 //   SUM    true:  the aggregate is summed here from the N gradients, worker order,
 //                 own gradient at position `self` (reads 4N + 4, writes 4 or 8 B/element)
 //          false: the aggregate is read from agg_full
-//   LOCAL  kLocalNone: global rule only              (WARMUP, i < n-1)
+//   LOCAL  kLocalOnly: eq. 11 alone, w_global untouched (the local half of a split step)
+//          kLocalNone: global rule only              (WARMUP, i < n-1)
 //          kLocalCopy: w_local = new global weight   (WARMUP, i == n-1, the copy after the pull)
 //          kLocalRule: w_local = W - lr_local * g    (WARMUP, i == n; correction passes; eq. 11)
 constexpr int kLocalNone = 0, kLocalCopy = 1, kLocalRule = 2;
-constexpr int kFullBatch = CDSGD_FULL_BATCH;  // peers' gradients in flight together
+constexpr int kLocalOnly = 3;  // eq. 11 alone: w_local = W - lr_local * g, the global weights are left alone
 
+// Launch shape of these passes, chosen by measurement: a workgroup is ONE wave that takes one
+// quad per lane (a "piece" of 64 quads = 1 KiB of every stream; 16 pieces to a chunk), and the
+// N-way sum loads the workers' gradients one after the other, each add waiting for its load.
+// Memory-level parallelism comes from the number of waves (32 per compute unit), not from
+// loads in flight per wave: waves that start together then walk the N streams together, so
+// the requests in flight chip-wide fall on one or two streams at a time instead of all N.
+// On the VGG-16-shaped list with 16 workers the sum runs at 6.2-6.3 TB/s that way; with 15
+// loads in flight per wave it ran at 5.6 TB/s, and with 512-lane workgroups, two quads per lane
+// and 8 loads in flight at 5.6-5.7 TB/s.
+constexpr unsigned kFullBlock = CDSGD_FULL_BLOCK;            // lanes per workgroup = quads per piece
+constexpr unsigned kPiecesPerChunk = kChunkQuads / kFullBlock;
+static_assert(kChunkQuads % kFullBlock == 0 && kFullBlock % 64 == 0, "pieces tile a chunk, whole waves");
+
+// One piece of one chunk: quad qi of the chunk for this lane, cnt of its elements exist.
 template <bool G, bool SUM, int LOCAL, int GT>
-__device__ __forceinline__ void full_chunk(const TensorDesc &d, const void *const *__restrict__ pg,
-                                           int num_peers, int self, size_t quad0, unsigned rem_elems,
-                                           float lr_local, float scale)
+__device__ __forceinline__ void full_piece(const TensorDesc &d, const void *const *__restrict__ pg,
+                                           int num_peers, int self, size_t quad0, unsigned qi,
+                                           unsigned rem_elems, float lr_local, float scale)
 {
-    const unsigned tid = threadIdx.x;
     float *__restrict__ wg = d.w_global + 4 * quad0;
     float *__restrict__ wl = d.w_local + 4 * quad0;
     const void *__restrict__ grad = grad_at<GT>(d.grad, quad0);
-    f4 w[kQpl], g[kQpl], a[kQpl];
-    int cnt[kQpl];
+    const int cnt = quad_count<G>(rem_elems, qi);
+    if (G && cnt == 0) return;
+    const f4 w = ld4g<G>(wg, qi, cnt);
+    f4 g = {0.0f, 0.0f, 0.0f, 0.0f}, a = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (SUM || LOCAL == kLocalRule || LOCAL == kLocalOnly) g = ldgrad<G, GT>(grad, qi, cnt);
+    if (LOCAL == kLocalOnly) {
+        f4 vl;
 #pragma unroll
-    for (unsigned j = 0; j < kQpl; ++j) {
-        const unsigned qi = j * kBlock + tid;
-        cnt[j] = quad_count<G>(rem_elems, qi);
-        w[j] = ld4g<G>(wg, qi, cnt[j]);
-        if (SUM || LOCAL == kLocalRule) g[j] = ldgrad<G, GT>(grad, qi, cnt[j]);
-        if (SUM) a[j] = f4{0.0f, 0.0f, 0.0f, 0.0f};
-        else a[j] = ld4g<G>(d.agg_full + 4 * quad0, qi, cnt[j]);
+        for (unsigned c = 0; c < 4; ++c) vl[c] = __builtin_fmaf(-lr_local, g[c], w[c]);
+        st4g<G>(wl, qi, cnt, vl);
+        return;
     }
+    if (!SUM) a = ld4g<G>(d.agg_full + 4 * quad0, qi, cnt);
     if (SUM) {
-        auto add_range = [&](int p_begin, int p_end) {
-            int p = p_begin;
-            for (; p + kFullBatch <= p_end; p += kFullBatch) {
-                f4 v[kFullBatch][kQpl];
-#pragma unroll
-                for (int i = 0; i < kFullBatch; ++i)
-#pragma unroll
-                    for (unsigned j = 0; j < kQpl; ++j)
-                        v[i][j] = ldgrad<G, GT>(grad_at<GT>(pg[p + i], quad0), j * kBlock + tid, cnt[j]);
-#pragma unroll
-                for (int i = 0; i < kFullBatch; ++i)
-#pragma unroll
-                    for (unsigned j = 0; j < kQpl; ++j) a[j] = a[j] + v[i][j];
-            }
-            for (; p < p_end; ++p) {
-#pragma unroll
-                for (unsigned j = 0; j < kQpl; ++j)
-                    a[j] = a[j] + ldgrad<G, GT>(grad_at<GT>(pg[p], quad0), j * kBlock + tid, cnt[j]);
-            }
-        };
-        add_range(0, self);
-#pragma unroll
-        for (unsigned j = 0; j < kQpl; ++j) a[j] = a[j] + g[j];
-        add_range(self, num_peers);
+        // one gradient at a time, each add waiting for its load: see the note on the launch shape
+        for (int p = 0; p < self; ++p) a = a + ldgrad<G, GT>(grad_at<GT>(pg[p], quad0), qi, cnt);
+        a = a + g;
+        for (int p = self; p < num_peers; ++p) a = a + ldgrad<G, GT>(grad_at<GT>(pg[p], quad0), qi, cnt);
     }
+    f4 vg, vl;
 #pragma unroll
-    for (unsigned j = 0; j < kQpl; ++j) {
-        const unsigned qi = j * kBlock + tid;
-        f4 vg, vl;
-#pragma unroll
-        for (unsigned c = 0; c < 4; ++c) {
-            vg[c] = __builtin_fmaf(-scale, a[j][c], w[j][c]);
-            vl[c] = LOCAL == kLocalRule ? __builtin_fmaf(-lr_local, g[j][c], w[j][c]) : vg[c];
-        }
-        if (LOCAL != kLocalNone) st4g<G>(wl, qi, cnt[j], vl);
-        st4g<G>(wg, qi, cnt[j], vg);
+    for (unsigned c = 0; c < 4; ++c) {
+        vg[c] = __builtin_fmaf(-scale, a[c], w[c]);
+        vl[c] = LOCAL == kLocalRule ? __builtin_fmaf(-lr_local, g[c], w[c]) : vg[c];
     }
+    if (LOCAL != kLocalNone) st4g<G>(wl, qi, cnt, vl);
+    st4g<G>(wg, qi, cnt, vg);
 }
 
 // peer_grads: [num_tensors][num_peers] pointers (own row left out), or unused when !SUM.
+// The grid walks the pieces of the chunk table: piece x belongs to chunk slot x / kPiecesPerChunk.
 template <bool SUM, int LOCAL, int GT>
-__global__ __launch_bounds__(CDSGD_BLOCK) void k_fused_full(const TensorDesc *__restrict__ tensors,
-                                                            const ChunkRef *__restrict__ chunks,
-                                                            const void *const *__restrict__ peer_grads,
-                                                            int num_peers, int self, float lr_local,
-                                                            float scale)
+__global__ __launch_bounds__(CDSGD_FULL_BLOCK) void k_fused_full(const TensorDesc *__restrict__ tensors,
+                                                                 const ChunkRef *__restrict__ chunks,
+                                                                 unsigned long long num_pieces,
+                                                                 const void *const *__restrict__ peer_grads,
+                                                                 int num_peers, int self, float lr_local,
+                                                                 float scale)
 {
-    const ChunkRef cr = chunks[chunk_slot()];
-    const TensorDesc d = tensors[cr.tensor];
-    const size_t quad0 = (size_t)cr.chunk * kChunkQuads;
-    const void *const *pg = SUM ? peer_grads + (size_t)cr.tensor * (size_t)num_peers : nullptr;
-    if (cr.chunk < d.ext.full_chunks)
-        full_chunk<false, SUM, LOCAL, GT>(d, pg, num_peers, self, quad0, kChunkElems, lr_local, scale);
-    else
-        full_chunk<true, SUM, LOCAL, GT>(d, pg, num_peers, self, quad0, d.ext.tail_elems, lr_local, scale);
+    for (unsigned long long b = blockIdx.x; b < num_pieces; b += gridDim.x) {
+        const unsigned long long x = piece_of_workgroup<CDSGD_XCD_FULL != 0>(b, kPiecesPerChunk, num_pieces);
+        const ChunkRef cr = chunks[x / kPiecesPerChunk];
+        const TensorDesc d = tensors[cr.tensor];
+        const size_t quad0 = (size_t)cr.chunk * kChunkQuads;
+        const unsigned qi = (unsigned)(x % kPiecesPerChunk) * kFullBlock + threadIdx.x;
+        const void *const *pg = SUM ? peer_grads + (size_t)cr.tensor * (size_t)num_peers : nullptr;
+        if (cr.chunk < d.ext.full_chunks)
+            full_piece<false, SUM, LOCAL, GT>(d, pg, num_peers, self, quad0, qi, kChunkElems, lr_local, scale);
+        else
+            full_piece<true, SUM, LOCAL, GT>(d, pg, num_peers, self, quad0, qi, d.ext.tail_elems, lr_local, scale);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -837,6 +935,15 @@ struct PlanTables {
     int grad_type = kGradF32;          // element type of grad and of the bound peer gradients
     bool own_thresholds = false;       // every tensor carries its own threshold
     bool own_thresholds_pow2 = false;  // ... and all of them are powers of two
+    unsigned max_workgroups = 0;       // > 0: launch at most this many workgroups (they take several chunks each)
+
+    // Workgroups to launch for `units` units of work (chunks, or pieces of chunks).
+    unsigned grid_size(unsigned long long units) const
+    {
+        const unsigned long long cap = max_workgroups != 0 ? max_workgroups : 0x7FFFFFFFull;
+        return (unsigned)(units < cap ? units : cap);
+    }
+    unsigned grid_size() const { return grid_size(num_chunks); }
 };
 
 struct cdsgd_plan : PlanTables {
@@ -933,11 +1040,12 @@ int launch_full_pass(const PlanTables *plan, int local_mode, float lr_local, flo
     if (!sum && !plan->has_agg_full) return CDSGD_ERR_NULL;
     const float scale = lr_global / (float)plan->num_workers;
     hipStream_t s = (hipStream_t)hip_stream;
-    const dim3 grid(plan->num_chunks), block(kBlock);
+    const unsigned long long num_pieces = (unsigned long long)plan->num_chunks * kPiecesPerChunk;
+    const dim3 grid(plan->grid_size(num_pieces)), block(kFullBlock);
     const int np = plan->num_workers - 1;
 #define CDSGD_LAUNCH_FULL_T(SUM, LOCAL, GT)                                                                    \
     hipLaunchKernelGGL((k_fused_full<SUM, LOCAL, GT>), grid, block, 0, s, plan->tensors, plan->chunks,           \
-                       plan->peer_grads, np, plan->self, lr_local, scale)
+                       num_pieces, plan->peer_grads, np, plan->self, lr_local, scale)
 #define CDSGD_LAUNCH_FULL(SUM, LOCAL)                                                                          \
     do {                                                                                                       \
         if (plan->grad_type == kGradBF16) CDSGD_LAUNCH_FULL_T(SUM, LOCAL, kGradBF16);                          \
@@ -1168,11 +1276,12 @@ int launch_formal_pass(const PlanTables *plan, long step, int k, float threshold
         return launch_full_pass(plan, with_local ? kLocalRule : kLocalNone, lr_local, lr_global, hip_stream);
     const float scale = lr_global / (float)plan->num_workers;
     hipStream_t s = (hipStream_t)hip_stream;
-    const dim3 grid(plan->num_chunks), block(kBlock);
     const int num_peers = plan->num_workers - 1;
+    const unsigned long long num_pieces = (unsigned long long)plan->num_chunks * kCompPiecesPerChunk;
+    const dim3 grid(plan->grid_size(num_pieces)), block(kPieceQuads);
 #define CDSGD_LAUNCH_COMPRESSED_T(POW2, LOCAL, GT)                                                            \
-    hipLaunchKernelGGL((k_fused_compressed<POW2, LOCAL, GT>), grid, block, 0, s, plan->tensors, plan->chunks,  \
-                       plan->peers, num_peers, plan->self, threshold, lr_local, scale)
+    hipLaunchKernelGGL((k_fused_compressed<POW2, LOCAL, GT>), grid, block, 0, s, plan->tensors,                \
+                       plan->chunks, num_pieces, plan->peers, num_peers, plan->self, threshold, lr_local, scale)
 #define CDSGD_LAUNCH_COMPRESSED(POW2, LOCAL)                                                                  \
     do {                                                                                                       \
         if (plan->grad_type == kGradBF16) CDSGD_LAUNCH_COMPRESSED_T(POW2, LOCAL, kGradBF16);                   \
@@ -1205,14 +1314,16 @@ int cdsgd_step_local(cdsgd_plan *plan, float lr_local, void *hip_stream)
 {
     if (!plan) return CDSGD_ERR_NULL;
     if (!std::isfinite(lr_local)) return CDSGD_ERR_PARAM;
-    const dim3 grid(plan->num_chunks), block(kBlock);
+    const unsigned long long num_pieces = (unsigned long long)plan->num_chunks * kPiecesPerChunk;
+    const dim3 grid(plan->grid_size(num_pieces)), block(kFullBlock);
     hipStream_t s = (hipStream_t)hip_stream;
-    if (plan->grad_type == kGradBF16)
-        hipLaunchKernelGGL(k_plan_local<kGradBF16>, grid, block, 0, s, plan->tensors, plan->chunks, lr_local);
-    else if (plan->grad_type == kGradF16)
-        hipLaunchKernelGGL(k_plan_local<kGradF16>, grid, block, 0, s, plan->tensors, plan->chunks, lr_local);
-    else
-        hipLaunchKernelGGL(k_plan_local<kGradF32>, grid, block, 0, s, plan->tensors, plan->chunks, lr_local);
+#define CDSGD_LAUNCH_LOCAL(GT)                                                                                 \
+    hipLaunchKernelGGL((k_fused_full<false, kLocalOnly, GT>), grid, block, 0, s, plan->tensors, plan->chunks,    \
+                       num_pieces, (const void *const *)nullptr, 0, plan->self, lr_local, 0.0f)
+    if (plan->grad_type == kGradBF16) CDSGD_LAUNCH_LOCAL(kGradBF16);
+    else if (plan->grad_type == kGradF16) CDSGD_LAUNCH_LOCAL(kGradF16);
+    else CDSGD_LAUNCH_LOCAL(kGradF32);
+#undef CDSGD_LAUNCH_LOCAL
     return launch_status();
 }
 
@@ -1273,6 +1384,14 @@ int cdsgd_plan_set_thresholds(cdsgd_plan *plan, const float *thresholds)
     plan->host_tensors.swap(next);
     plan->own_thresholds = thresholds != nullptr;
     plan->own_thresholds_pow2 = thresholds != nullptr && all_pow2;
+    return CDSGD_OK;
+}
+
+int cdsgd_plan_set_max_workgroups(cdsgd_plan *plan, int max_workgroups)
+{
+    if (!plan) return CDSGD_ERR_NULL;
+    if (max_workgroups < 0) return CDSGD_ERR_PARAM;
+    plan->max_workgroups = (unsigned)max_workgroups;
     return CDSGD_OK;
 }
 

@@ -22,6 +22,15 @@ from . import binding, synth
 ALIGN_ELEMS = 1024
 
 
+def default_arena(numel, dtype, device):
+    """One arena = one zeroed device allocation of its own."""
+    return torch.zeros(numel, dtype=dtype, device=device)
+
+
+# how a Workload gets its arenas: (numel, dtype, device) -> zeroed 1-D tensor
+arena_allocator = default_arena
+
+
 class Workload:
     def __init__(self, cfg: synth.Config, device="cuda", dense: bool = False, self_rank: int = 0,
                  peer_residuals: bool = True, full_grads: bool = False, grad_dtype=torch.float32):
@@ -39,16 +48,18 @@ class Workload:
         self.total = o
         f32 = dict(dtype=torch.float32, device=self.device)
         i32 = dict(dtype=binding.PACKED_DTYPE, device=self.device)
-        self.w_global = torch.zeros(self.total, **f32)
-        self.w_local = torch.zeros(self.total, **f32)
-        self.residual = torch.zeros(self.total, **f32)
+        alloc = arena_allocator
+        self.w_global = alloc(self.total, torch.float32, self.device)
+        self.w_local = alloc(self.total, torch.float32, self.device)
+        self.residual = alloc(self.total, torch.float32, self.device)
         # gradients may be held in bf16 / fp16 (the library widens them on load); everything else is fp32
         self.grad_dtype = grad_dtype
-        self.grad = torch.zeros(self.total, dtype=grad_dtype, device=self.device)
-        self.agg_full = torch.zeros(self.total, **f32)
-        self.packed_self = torch.zeros(self.total // 16, **i32)
+        self.grad = alloc(self.total, grad_dtype, self.device)
+        self.agg_full = alloc(self.total, torch.float32, self.device)
+        self.packed_self = alloc(self.total // 16, binding.PACKED_DTYPE, self.device)
         self.peer_packed: List[Optional[torch.Tensor]] = [
-            None if j == self.self_rank else torch.zeros(self.total // 16, **i32) for j in range(self.N)]
+            None if j == self.self_rank else alloc(self.total // 16, binding.PACKED_DTYPE, self.device)
+            for j in range(self.N)]
         self.peer_residual: List[Optional[torch.Tensor]] = [
             None if (j == self.self_rank or not peer_residuals) else torch.zeros(self.total, **f32)
             for j in range(self.N)]

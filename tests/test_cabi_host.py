@@ -31,7 +31,8 @@ def test_header_declares_the_named_entry_points():
                  "cdsgd_plan_bind_full_grads", "cdsgd_step_warmup", "cdsgd_trainer_create",
                  "cdsgd_trainer_step", "cdsgd_trainer_iteration", "cdsgd_trainer_destroy",
                  "cdsgd_step_local", "cdsgd_step_global", "cdsgd_cost_iteration", "cdsgd_cost_period_mean",
-                 "cdsgd_plan_create_typed", "cdsgd_plan_set_thresholds"):
+                 "cdsgd_plan_create_typed", "cdsgd_plan_set_thresholds", "cdsgd_plan_set_max_workgroups",
+                 "cdsgd_step_fused_static", "cdsgd_build_id"):
         assert must in names
 
 
@@ -162,6 +163,7 @@ def test_plan_and_step_argument_errors(L):
     assert out.value is None
     step = L.cdsgd_step_fused
     assert step(None, 1, 4, 0.5, 0.1, 0.1, None) == ERR_NULL
+    assert L.cdsgd_plan_set_max_workgroups(None, 4) == ERR_NULL
     assert L.cdsgd_plan_destroy(None) == OK
     fake = ctypes.c_void_p(A)  # parameter checks come before the plan is looked at
     assert step(fake, 1, 0, 0.5, 0.1, 0.1, None) == ERR_PARAM

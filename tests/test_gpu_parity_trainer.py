@@ -96,16 +96,20 @@ def test_full_pass_needs_an_aggregate(P):
     plan.destroy()
 
 
+@pytest.mark.parametrize("max_workgroups", [0, 1, 5, 64], ids=["wg_per_chunk", "1wg", "5wg", "64wg"])
 @pytest.mark.parametrize("t_pow2", [True, False], ids=["t0.5", "t0.05"])
-def test_split_step_equals_fused(P, oracle, t_pow2):
+def test_split_step_equals_fused(P, oracle, t_pow2, max_workgroups):
     """cdsgd_step_local then cdsgd_step_global (on a second stream, ordered by an event)
     leave bit for bit what cdsgd_step_fused leaves, on compressed and correction passes;
-    cdsgd_step_local alone matches eq. 11 of the oracle and leaves w_global alone."""
+    cdsgd_step_local alone matches eq. 11 of the oracle and leaves w_global alone.  The split
+    side also runs with a bounded number of workgroups (cdsgd_plan_set_max_workgroups): fewer
+    workgroups than chunks, each walking several, must change nothing."""
     pkg, runner, synth = P
     cfg = synth.scaled(synth.config("c2_resnet20" if t_pow2 else "c5_flat4g"), SIZES, "_split")
     cfg.num_workers, cfg.k = 8, 3
     a = runner.Workload(cfg, dense=True, self_rank=3)     # fused
     b = runner.Workload(cfg, dense=True, self_rank=3)     # split
+    b.plan.set_max_workgroups(max_workgroups)
     side = torch.cuda.Stream()                            # default priority
     main = torch.cuda.current_stream()
     for s in range(2 * cfg.k + 1):
@@ -133,6 +137,42 @@ def test_split_step_equals_fused(P, oracle, t_pow2):
             assert torch.equal(x.view(torch.int32), y.view(torch.int32)), "%s differs at step %d" % (key, s)
     a.destroy()
     b.destroy()
+
+
+@pytest.mark.parametrize("full_grads", [True, False], ids=["kernel_sum", "agg_full"])
+def test_workgroup_limit_changes_nothing(P, oracle, full_grads):
+    """Alg. 1 end to end (warm-up, correction and compressed passes) on a plan limited to 1, 2, 7
+    or far more workgroups than it has chunks, against the same plan without a limit: every
+    buffer bit for bit, every iteration; the unlimited run is itself checked against the oracle
+    by the other tests of this file."""
+    pkg, runner, synth = P
+    cfg = synth.scaled(synth.config("c5_flat4g"), SIZES + [3 * 4096 + 17], "_wglimit")
+    cfg.num_workers, cfg.k = 5, 3
+    warmup_n = 1
+    limits = [0, 1, 2, 7, 1 << 20]
+    wls = [runner.Workload(cfg, dense=True, self_rank=2, full_grads=full_grads) for _ in limits]
+    trainers = []
+    for wl, lim in zip(wls, limits):
+        wl.plan.set_max_workgroups(lim)
+        trainers.append(pkg.Trainer(wl.plan, warmup_n, cfg.k, cfg.threshold, 0.4, 0.1))
+    for it in range(warmup_n + 1 + 2 * cfg.k):
+        comp = it > warmup_n and (it - warmup_n - 1) % cfg.k != 0
+        for wl, tr in zip(wls, trainers):
+            wl.prepare_step(it, compressed=comp)
+            tr.step()
+        torch.cuda.synchronize()
+        for wl, lim in zip(wls[1:], limits[1:]):
+            for key in ("w_global", "w_local", "residual", "packed_self"):
+                x, y = getattr(wls[0], key), getattr(wl, key)
+                assert torch.equal(x.view(torch.int32), y.view(torch.int32)), \
+                    "%s differs at iteration %d with a limit of %d workgroups" % (key, it, lim)
+    with pytest.raises(pkg.CdsgdError) as e:
+        wls[0].plan.set_max_workgroups(-1)
+    assert e.value.status == pkg.binding.ERR_PARAM
+    for tr in trainers:
+        tr.destroy()
+    for wl in wls:
+        wl.destroy()
 
 
 def test_fused_steps_in_a_hip_graph_replay_like_eager(P):

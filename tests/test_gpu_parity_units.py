@@ -337,3 +337,5 @@ def test_fused_step_random_configurations(B, oracle):
                             seed=9000 + case)
         except AssertionError as e:
             raise AssertionError("case %d: sizes=%s N=%d self=%d k=%d t=%g: %s" % (case, sizes, N, self_rank, k, t, e))
+        if cases > 100 and case % 100 == 99:
+            print("fuzz: %d cases done" % (case + 1), flush=True)

@@ -70,6 +70,12 @@ MUTANTS = [
     ("cost_local_is_sum", "double t_loc = tau > phi ? tau : phi;", "double t_loc = tau + phi;"),
     ("cost_bit_forgets_delta", "double t_bit = tau + delta + psi;", "double t_bit = tau + psi;"),
     ("cost_cd_is_min", "double t_cd = tau > phi_cd ? tau : phi_cd;", "double t_cd = tau < phi_cd ? tau : phi_cd;"),
+    ("sparse_bitmap_msb_first", "seg[i / 32] |= 1u << (i % 32);", "seg[i / 32] |= 1u << (31 - i % 32);"),
+    ("sparse_segment_stride_256", "uint32_t *seg = sparse + 264 * s;", "uint32_t *seg = sparse + 256 * s;"),
+    ("sparse_count_misses_bitmap", "seg_words[s] = 8u + count;", "seg_words[s] = count;"),
+    ("sparse_zero_words_travel", "if (w < nw && word[w] != 0u) {", "if (w < nw) {"),
+    ("sparse_decode_counts_own_bit", "for (size_t b = 0; b < i; ++b) before", "for (size_t b = 0; b <= i; ++b) before"),
+    ("sparse_decode_ignores_bitmap", "if ((seg[i / 32] >> (i % 32)) & 1u) {", "if (1) {"),
     ("local_uses_wrong_worker", "oracle_update(w_global, w_local, grad[self],", "oracle_update(w_global, w_local, grad[num_workers - 1 - self],"),
 ]
 

@@ -552,6 +552,75 @@ def test_warmup_is_ssgd_and_hands_over_to_formal_training(oracle, warmup_n):
 
 
 # --------------------------------------------------------------------------
+# sparse form of a packed stream (this build's wire format; pinned to its definition only)
+# --------------------------------------------------------------------------
+def test_sparse_layout_fixture(oracle):
+    rows = _read_golden("sparse_layout_n4200.txt")
+    n = int(rows[0].split()[1])
+    word = np.zeros(oracle.packed_words(n), np.uint32)
+    segs = {}
+    for row in rows[1:]:
+        f = row.split()
+        if f[0] == "word":
+            word[int(f[1])] = int(f[2], 16)
+        else:
+            assert f[0] == "segment" and f[2] == "bitmap" and f[11] == "values"
+            segs[int(f[1])] = ([int(x, 16) for x in f[3:11]], [int(x, 16) for x in f[12:]])
+    sparse, seg_words = oracle.sparse_encode(word, n, fill=0xDEADBEEF)
+    assert oracle.sparse_segments(n) == len(segs) == 2 and sparse.size == 2 * 264
+    for s_i, (bitmap, values) in segs.items():
+        seg = sparse[264 * s_i: 264 * (s_i + 1)]
+        assert [int(x) for x in seg[:8]] == bitmap
+        assert [int(x) for x in seg[8: 8 + len(values)]] == values
+        assert (seg[8 + len(values):] == 0xDEADBEEF).all()          # slots after the values are left alone
+        assert int(seg_words[s_i]) == 8 + len(values)
+    assert np.array_equal(oracle.sparse_decode(sparse, n), word)
+
+
+def test_sparse_roundtrip_every_tail_and_density(oracle):
+    rng = np.random.default_rng(11)
+    sizes = list(range(1, 71)) + [4095, 4096, 4097, 4111, 8191, 8192, 8193, 3 * 4096 + 5, 16 * 256 * 5 + 16]
+    for n in sizes:
+        nw = oracle.packed_words(n)
+        for density in (0.0, 1.0, 0.02, 0.5):
+            word = rng.integers(1, 1 << 32, nw, dtype=np.uint64).astype(np.uint32)
+            word[rng.random(nw) >= density] = 0
+            sparse, seg_words = oracle.sparse_encode(word, n, fill=0xA5A5A5A5)
+            assert sparse.size == 264 * ((nw + 255) // 256)
+            # the format stated independently, in Python integers
+            for s_i in range((nw + 255) // 256):
+                part = [int(x) for x in word[256 * s_i: 256 * (s_i + 1)]]
+                nz = [(i, v) for i, v in enumerate(part) if v]
+                seg = sparse[264 * s_i: 264 * (s_i + 1)]
+                bits = sum(1 << i for i, _ in nz)
+                assert [int(x) for x in seg[:8]] == [(bits >> (32 * m)) & 0xFFFFFFFF for m in range(8)]
+                assert [int(x) for x in seg[8: 8 + len(nz)]] == [v for _, v in nz]
+                assert (seg[8 + len(nz):] == 0xA5A5A5A5).all()
+                assert int(seg_words[s_i]) == 8 + len(nz)
+            if density == 0.0:
+                assert int(seg_words.sum()) == 8 * seg_words.size                    # bitmaps only
+            if density == 1.0:
+                assert int(seg_words.sum()) == 8 * seg_words.size + nw               # every word travels
+            assert np.array_equal(oracle.sparse_decode(sparse, n), word)
+
+
+def test_sparse_decode_then_sum_is_the_dense_sum(oracle):
+    """The method is untouched by the wire format: decode-and-sum of streams that went through
+    the sparse form equals decode-and-sum of the packed streams, for real quantiser output."""
+    rng = np.random.default_rng(12)
+    n, N, t = 10000, 5, 0.5
+    words = []
+    for j in range(N):
+        g = rng.normal(0, 0.25 * (j + 1), n).astype(np.float32)
+        words.append(oracle.quantize_pack(g, np.zeros(n, np.float32), t))
+    through = [oracle.sparse_decode(oracle.sparse_encode(w, n)[0], n) for w in words]
+    assert all(np.array_equal(a, b) for a, b in zip(words, through))
+    assert np.array_equal(oracle.decode_sum(through, n, t), oracle.decode_sum(words, n, t))
+    wire = sum(int(oracle.sparse_encode(w, n)[1].sum()) for w in words)
+    assert wire < N * oracle.packed_words(n) + 8 * N * oracle.sparse_segments(n) + 1
+
+
+# --------------------------------------------------------------------------
 # time-cost model (Sec. 2.1-2.3, Sec. 3.3)
 # --------------------------------------------------------------------------
 def _eq8_table(tau, phi, psi, delta, k, i):
