@@ -33,8 +33,9 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per k_fused_compressed launch.  NOT measured by this run: constants taken from earlier
 # rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this file, scaled by the same counters' readings
 # for a 1 GiB device copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 on this GPU); the summaries are
-# profiles/k_fused_compressed_<workload>.md.
-PROFILED_TRAFFIC_BYTES = {"c4_vgg16": 3.8786e9, "c3_resnet50": 0.7170e9}
+# profiles/k_fused_compressed_<workload>.md (c3_resnet50: read side from the current kernel, write
+# side from an earlier build with the same stores).
+PROFILED_TRAFFIC_BYTES = {"c4_vgg16": 3.8786e9, "c3_resnet50": 0.7169e9, "c5_flat4g": 30.098e9}
 MIN_TIMED_SECONDS = 1.0     # sustained: the timed blocks of the headline cover at least this much GPU time
 MIN_BLOCKS = 10
 
@@ -219,7 +220,7 @@ def time_small(name, steps=200):
             "note": "one period of k steps (1 correction + k-1 compressed) per graph; wall clock incl. launch"}
 
 
-def time_correction_sum(name, steps, warmup):
+def time_correction_sum(name, steps, warmup, min_seconds=0.5):
     """Correction pass that sums the N workers' fp32 gradients in the kernel (Alg. 1, else-branch):
     reads W and N gradients, writes W and W_loc = 12 + 4N bytes per element."""
     import torch
@@ -230,7 +231,7 @@ def time_correction_sum(name, steps, warmup):
     stream = torch.cuda.current_stream()
     for _ in range(max(warmup, 1)):
         wl.fused_step(0)
-    blocks = timed_blocks(lambda: [wl.fused_step(0) for _ in range(steps)], steps, stream, min_seconds=0.5,
+    blocks = timed_blocks(lambda: [wl.fused_step(0) for _ in range(steps)], steps, stream, min_seconds=min_seconds,
                           min_blocks=5)
     ms = blocks["median_ms_per_step"]
     bpe = 12.0 + 4.0 * cfg.num_workers
@@ -248,7 +249,7 @@ def overlap_demo(name, iters=16):
     cdsgd_step_global is run with one workgroup per chunk and with bounded grids
     (cdsgd_plan_set_max_workgroups), which leave compute units to the stand-in.  Two stand-ins:
     one bf16 matrix product that fills every compute unit, and a chain of small products that
-    does not (a forward pass bound by launch latency)."""
+    does not (a small-batch forward pass)."""
     import torch
     from paper_2106_10796_amd import runner, synth
     cfg = synth.config(name)
@@ -284,12 +285,44 @@ def overlap_demo(name, iters=16):
             y = torch.randn(M, M, device="cuda", dtype=torch.bfloat16)
             z = torch.empty(M, M, device="cuda", dtype=torch.bfloat16)
             return "one bf16 %dx%dx%d matrix product" % (M, M, M), lambda: torch.mm(x, y, out=z)
+        # a forward pass that does NOT fill the chip: small products (at most 64 output tiles each), replayed
+        # from a HIP graph so that the GPU, not the host's launch rate, sets their pace
         M, reps = 1024, 48
         x = torch.randn(M, M, device="cuda", dtype=torch.bfloat16)
         y = torch.randn(M, M, device="cuda", dtype=torch.bfloat16)
         z = torch.empty(M, M, device="cuda", dtype=torch.bfloat16)
-        return "%d bf16 %dx%dx%d matrix products in a row" % (reps, M, M, M), \
-            lambda: [torch.mm(x, y, out=z) for _ in range(reps)]
+        label = "%d bf16 %dx%dx%d matrix products in a row" % (reps, M, M, M)
+        try:
+            cap = torch.cuda.Stream()
+            cap.wait_stream(main)
+            with torch.cuda.stream(cap):
+                for _ in range(3):
+                    torch.mm(x, y, out=z)
+            main.wait_stream(cap)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=cap):
+                for _ in range(reps):
+                    torch.mm(x, y, out=z)
+            torch.cuda.synchronize()
+            return label + ", replayed from a HIP graph", graph.replay
+        except Exception as exc:                         # capture not possible: launch them one by one
+            return label + " (eager: graph capture failed: %s)" % type(exc).__name__, \
+                lambda: [torch.mm(x, y, out=z) for _ in range(reps)]
+
+    def masked_stream(word):
+        """A default-priority stream whose kernels may only run on the compute units named by a mask
+        (hipExtStreamCreateWithCUMask): the same 32-bit word for each of 8 groups of 32 compute units."""
+        import ctypes
+        try:
+            hip = ctypes.CDLL("libamdhip64.so")
+            st = ctypes.c_void_p()
+            arr = (ctypes.c_uint32 * 8)(*([word] * 8))
+            if hip.hipExtStreamCreateWithCUMask(ctypes.byref(st), 8, arr) != 0 or not st.value:
+                return None
+            return torch.cuda.ExternalStream(st.value), (hip, st)
+        except Exception:
+            return None
 
     wl.plan.set_max_workgroups(0)
     out = {"workload": name,
@@ -299,7 +332,7 @@ def overlap_demo(name, iters=16):
            "stand_ins": {}}
     out["forward_can_start_after_ms"] = {"fused": out["ms_fused_step"], "split": out["ms_step_local"]}
     limits = [0, 4096, 2048, 1024, 512, 256]
-    for kind in ("full_chip", "latency_bound"):
+    for kind in ("full_chip", "partial_chip"):
         label, forward = make_stand_in(kind)
 
         def fused_then_forward():
@@ -313,7 +346,7 @@ def overlap_demo(name, iters=16):
                 forward()
                 wl.plan.step_global(s, cfg.k, cfg.threshold, cfg.lr)
 
-        def split_overlapped():
+        def split_overlapped(side=side):
             g_done = None
             for s in steps:
                 if g_done is not None:
@@ -341,10 +374,31 @@ def overlap_demo(name, iters=16):
                 "ms_iter_split_two_streams": timed(split_overlapped)}
         wl.plan.set_max_workgroups(0)
         r["two_streams_by_workgroup_limit_of_step_global"] = two
-        best = min(two, key=lambda q: two[q]["ms_iter_split_two_streams"])
-        r["best_two_streams"] = {"workgroup_limit": best, "ms_iter": two[best]["ms_iter_split_two_streams"],
-                                 "vs_fused_then_forward": two[best]["ms_iter_split_two_streams"]
-                                 / r["ms_iter_fused_then_forward"]}
+        # the same schedule with cdsgd_step_global on a stream confined to a share of the compute units
+        masked = {}
+        for share, word in (("64_of_256_cus", 0x000000FF), ("128_of_256_cus", 0x0000FFFF), ("192_of_256_cus", 0x00FFFFFF)):
+            ms = masked_stream(word)
+            if ms is None:
+                masked[share] = None
+                continue
+            stream_m, (hip, handle) = ms
+
+            def global_on_masked():
+                with torch.cuda.stream(stream_m):
+                    for s in steps:
+                        wl.plan.step_global(s, cfg.k, cfg.threshold, cfg.lr)
+                main.wait_stream(stream_m)
+            stream_m.wait_stream(main)
+            masked[share] = {"ms_step_global_alone": timed(global_on_masked),
+                             "ms_iter_split_two_streams": timed(lambda: split_overlapped(stream_m))}
+            torch.cuda.synchronize()
+            hip.hipStreamDestroy(handle)
+        r["two_streams_with_step_global_on_a_cu_masked_stream"] = masked
+        cands = {("workgroup_limit", q): v["ms_iter_split_two_streams"] for q, v in two.items()}
+        cands.update({("cu_mask", q): v["ms_iter_split_two_streams"] for q, v in masked.items() if v})
+        best = min(cands, key=cands.get)
+        r["best_two_streams"] = {best[0]: best[1], "ms_iter": cands[best],
+                                 "vs_fused_then_forward": cands[best] / r["ms_iter_fused_then_forward"]}
         out["stand_ins"][kind] = r
     wl.destroy()
     return out
@@ -433,9 +487,15 @@ def main():
     ap.add_argument("--workload", default="c4_vgg16")
     ap.add_argument("--no-extra", action="store_true", help="skip the ResNet-50 and 4 GiB workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--min-seconds", type=float, default=MIN_TIMED_SECONDS,
+                    help="GPU time the timed blocks of the headline must cover (default %(default)s; profiler runs "
+                         "that collect counters per dispatch pass a small value to keep the dispatch count low)")
     ap.add_argument("--only-correction-sum", action="store_true",
                     help="time only the correction pass that sums the N gradients in the kernel (for profiling "
                          "k_fused_full<true, ...> on its own) and print its figures instead of the benchmark line")
+    ap.add_argument("--only-overlap", action="store_true",
+                    help="run only the overlap demo (split step on two streams beside a forward stand-in) and print "
+                         "its figures instead of the benchmark line")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain device copy of known size (1 GiB read + 1 GiB written, 3 times): "
                          "under rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings give the counters' scale")
@@ -461,13 +521,16 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
+    if args.only_overlap:
+        print(json.dumps(overlap_demo(args.workload)))
+        return 0
     if args.only_correction_sum:
-        r = time_correction_sum(args.workload, args.steps, args.warmup)
+        r = time_correction_sum(args.workload, args.steps, args.warmup, min_seconds=min(0.5, args.min_seconds))
         r["workload"] = args.workload
         print(json.dumps(r))
         return 0
     head, wl = time_workload(args.workload, args.steps, args.warmup, want_correction=True,
-                             want_unfused=not args.no_extra)
+                             want_unfused=not args.no_extra, min_seconds=args.min_seconds)
     ceilings = None if args.no_extra else stream_ceilings(wl)
     cpu = None
     if not args.no_cpu_baseline:
