@@ -211,6 +211,46 @@ int cdsgd_step_global(cdsgd_plan *plan, long step, int k, float threshold, float
                       void *hip_stream);
 
 /*
+ * Sparse form of a packed stream: a wire format of THIS LIBRARY, not of the paper, which names a
+ * combination with sparsification as future work (Sec. 7) and defines nothing; Sec. 2.3 observes
+ * that residuals stay below the threshold for long stretches, i.e. that most packed words are zero.
+ * The method is untouched: a sparse stream decodes to the packed stream word for word, so every
+ * aggregate and weight is bit-identical to the packed path.
+ *
+ * Format.  The cdsgd_packed_words(n) words of a stream are cut into segments of 256 words (4096
+ * elements); there are cdsgd_sparse_segments(n) = ceil(words / 256) of them.  Segment s occupies
+ * words [264 s, 264 s + 264) of the sparse buffer (cdsgd_sparse_words(n) = 264 x segments words in
+ * all): first 8 bitmap words -- bit b of bitmap word m is set iff packed word 256 s + 32 m + b
+ * exists and is non-zero -- then the non-zero packed words of the segment in index order.  The
+ * slots behind them are neither written nor read.  A sender puts the first
+ * segment_words[s] = 8 + (non-zero words) words of each segment on the wire.
+ *
+ *   cdsgd_sparse_encode      packed          in   uint32[cdsgd_packed_words(n)]
+ *                            sparse          out  uint32[cdsgd_sparse_words(n)]
+ *                            segment_words   out  uint32[cdsgd_sparse_segments(n)], may be NULL
+ *   cdsgd_decode_sum_sparse  cdsgd_decode_sum (Sec. 3.2.1; the sum of eq. 10) on streams in the
+ *                            sparse form: `sparse` is a HOST array of num_workers DEVICE pointers
+ *                            to uint32[cdsgd_sparse_words(n)]; same result, bit for bit, as
+ *                            cdsgd_decode_sum on the packed streams.
+ *   cdsgd_plan_set_peer_format   CDSGD_PEERS_SPARSE: the plan's peers[j][i] pointers are read as
+ *                            sparse buffers (cdsgd_sparse_words(n_i) words each) by compressed
+ *                            passes; CDSGD_PEERS_PACKED (the default) goes back.  packed_self is
+ *                            always written in the packed form.  Host-side setting; anything else
+ *                            is CDSGD_ERR_PARAM.  (The overlap checks of cdsgd_plan_create cover
+ *                            the packed extent of a peer's buffer only.)
+ * A compressed pass then reads 32 bytes + 4 bytes per non-zero word of each peer and chunk instead
+ * of 1024 bytes: 24.4 instead of 28 bytes per element at N = 16 when nothing is sent.
+ */
+typedef enum { CDSGD_PEERS_PACKED = 0, CDSGD_PEERS_SPARSE = 1 } cdsgd_peer_format;
+size_t cdsgd_sparse_segments(size_t n);
+size_t cdsgd_sparse_words(size_t n);
+int cdsgd_sparse_encode(const uint32_t *packed, size_t n, uint32_t *sparse, uint32_t *segment_words,
+                        void *hip_stream);
+int cdsgd_decode_sum_sparse(const uint32_t *const *sparse, int num_workers, float *agg, size_t n,
+                            float threshold, void *hip_stream);
+int cdsgd_plan_set_peer_format(cdsgd_plan *plan, int format);
+
+/*
  * Bound the number of workgroups that the passes of this plan launch (Sec. 3.2.2: the rest of
  * the step should not stand in the way of the next iteration's computation).  By default a
  * pass launches one workgroup per 4096-element chunk of the layer list and fills the GPU; with

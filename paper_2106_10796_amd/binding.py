@@ -84,6 +84,16 @@ def lib():
                                               i, i, i, ctypes.POINTER(vp)]
         L.cdsgd_plan_set_thresholds.restype = i
         L.cdsgd_plan_set_thresholds.argtypes = [vp, ctypes.POINTER(f)]
+        L.cdsgd_sparse_segments.restype = sz
+        L.cdsgd_sparse_segments.argtypes = [sz]
+        L.cdsgd_sparse_words.restype = sz
+        L.cdsgd_sparse_words.argtypes = [sz]
+        L.cdsgd_sparse_encode.restype = i
+        L.cdsgd_sparse_encode.argtypes = [vp, sz, vp, vp, vp]
+        L.cdsgd_decode_sum_sparse.restype = i
+        L.cdsgd_decode_sum_sparse.argtypes = [ctypes.POINTER(vp), i, vp, sz, f, vp]
+        L.cdsgd_plan_set_peer_format.restype = i
+        L.cdsgd_plan_set_peer_format.argtypes = [vp, i]
         L.cdsgd_plan_set_max_workgroups.restype = i
         L.cdsgd_plan_set_max_workgroups.argtypes = [vp, i]
         L.cdsgd_step_local.restype = i
@@ -164,6 +174,38 @@ def cdsgd_decode_sum(packed_list, agg, threshold):
     _check(st, "cdsgd_decode_sum")
 
 
+PEERS_PACKED, PEERS_SPARSE = 0, 1   # cdsgd_peer_format
+
+
+def sparse_segments(n: int) -> int:
+    return int(lib().cdsgd_sparse_segments(int(n)))
+
+
+def sparse_words(n: int) -> int:
+    return int(lib().cdsgd_sparse_words(int(n)))
+
+
+def new_sparse(n: int, device="cuda") -> torch.Tensor:
+    return torch.empty(sparse_words(n), dtype=PACKED_DTYPE, device=device)
+
+
+def cdsgd_sparse_encode(packed, n, sparse, segment_words=None):
+    st = lib().cdsgd_sparse_encode(_dev(packed, PACKED_DTYPE, packed_words(n), "packed"), int(n),
+                                   _dev(sparse, PACKED_DTYPE, sparse_words(n), "sparse"),
+                                   _dev(segment_words, PACKED_DTYPE, sparse_segments(n), "segment_words"), _stream())
+    _check(st, "cdsgd_sparse_encode")
+
+
+def cdsgd_decode_sum_sparse(sparse_list, agg, threshold):
+    n = agg.numel()
+    N = len(sparse_list)
+    arr = (ctypes.c_void_p * max(N, 1))()
+    for j, p in enumerate(sparse_list):
+        arr[j] = _dev(p, PACKED_DTYPE, sparse_words(n), "sparse[%d]" % j)
+    st = lib().cdsgd_decode_sum_sparse(arr, N, _dev(agg, torch.float32, None, "agg"), n, float(threshold), _stream())
+    _check(st, "cdsgd_decode_sum_sparse")
+
+
 def cdsgd_update(w_global, w_local, grad_local, agg, lr_local, lr_global, num_workers):
     n = w_global.numel()
     st = lib().cdsgd_update(_dev(w_global, torch.float32, None, "w_global"),
@@ -188,8 +230,9 @@ def cdsgd_cost_period_mean(tau, phi, psi, delta, k) -> dict:
     return out.as_dict()
 
 
-def _marshal_layer_list(tensors, peers, num_workers, grad_dtype):
+def _marshal_layer_list(tensors, peers, num_workers, grad_dtype, peers_sparse=False):
     """The C arrays of a layer list: (cdsgd_tensor[T], peers' row table or None, keep-alive list)."""
+    peer_words = sparse_words if peers_sparse else packed_words
     T = len(tensors)
     if grad_dtype not in GRAD_DTYPES:
         raise TypeError("gradients must be float32, bfloat16 or float16")
@@ -215,7 +258,7 @@ def _marshal_layer_list(tensors, peers, num_workers, grad_dtype):
         row = (ctypes.c_void_p * max(T, 1))()
         for i in range(T):
             n = tensors[i]["w_global"].numel()
-            row[i] = _dev(peers[j][i], PACKED_DTYPE, packed_words(n), "peers[%d][%d]" % (j, i)).value
+            row[i] = _dev(peers[j][i], PACKED_DTYPE, peer_words(n), "peers[%d][%d]" % (j, i)).value
         keep.append(row)
         rows[j] = ctypes.cast(row, ctypes.POINTER(ctypes.c_void_p))
     return arr, rows, keep
@@ -237,15 +280,16 @@ class Plan:
 
     tensors: list of dicts with keys w_global, w_local, residual, grad, packed_self and
     optionally agg_full (torch CUDA tensors).  peers: list over workers of lists over
-    tensors of packed tensors; the entry for `self_rank` may be None.  The plan keeps
+    tensors of packed tensors (sparse buffers with peers_sparse=True); the entry for `self_rank`
+    may be None.  The plan keeps
     references to every tensor so that the borrowed pointers stay valid.
     """
 
-    def __init__(self, tensors, peers, num_workers, self_rank, grad_dtype=torch.float32):
+    def __init__(self, tensors, peers, num_workers, self_rank, grad_dtype=torch.float32, peers_sparse=False):
         T = len(tensors)
         self._grad_dtype = grad_dtype
         self._keep = (tensors, peers)
-        arr, rows, self._rows = _marshal_layer_list(tensors, peers, num_workers, grad_dtype)
+        arr, rows, self._rows = _marshal_layer_list(tensors, peers, num_workers, grad_dtype, peers_sparse)
         self._sizes = [t["w_global"].numel() for t in tensors]
         handle = ctypes.c_void_p()
         if grad_dtype == torch.float32:
@@ -256,6 +300,8 @@ class Plan:
         _check(st, "cdsgd_plan_create")
         self._handle = handle
         self.num_workers = int(num_workers)
+        if peers_sparse:
+            self.set_peer_format(PEERS_SPARSE)
 
     def step(self, step, k, threshold, lr_local, lr_global):
         st = lib().cdsgd_step_fused(self._handle, int(step), int(k), float(threshold), float(lr_local),
@@ -272,6 +318,10 @@ class Plan:
             arr = (ctypes.c_float * len(thresholds))(*[float(x) for x in thresholds])
             st = lib().cdsgd_plan_set_thresholds(self._handle, arr)
         _check(st, "cdsgd_plan_set_thresholds")
+
+    def set_peer_format(self, fmt):
+        """PEERS_PACKED or PEERS_SPARSE: how compressed passes read the peers' streams (cdsgd_plan_set_peer_format)."""
+        _check(lib().cdsgd_plan_set_peer_format(self._handle, int(fmt)), "cdsgd_plan_set_peer_format")
 
     def set_max_workgroups(self, max_workgroups):
         """At most this many workgroups per pass (0: one per chunk); cdsgd_plan_set_max_workgroups."""

@@ -60,6 +60,9 @@
 #ifndef CDSGD_PIECE_WAVES
 #define CDSGD_PIECE_WAVES 4
 #endif
+#ifndef CDSGD_FEW_PEERS
+#define CDSGD_FEW_PEERS 8
+#endif
 #ifndef CDSGD_XCD_PIECES
 #define CDSGD_XCD_PIECES 1
 #endif
@@ -507,6 +510,141 @@ __global__ __launch_bounds__(CDSGD_BLOCK) void k_update(float *__restrict__ wg, 
     else update_chunk<true, LOCAL, GLOBAL>(wg, wl, grad, agg, ext.tail_elems, lr_local, scale);
 }
 
+typedef unsigned u4 __attribute__((ext_vector_type(4)));
+
+// values of the codes of a register, as 2-bit two's-complement fields (01 -> +1, 10 -> -1, else 0)
+__device__ __forceinline__ unsigned signed_fields(unsigned w)
+{
+    const unsigned x = w & 0x55555555u;
+    const unsigned y = (w >> 1) & 0x55555555u;
+    return (x ^ y) | ((y & ~x) << 1);
+}
+
+// ---------------------------------------------------------------------------
+// Sparse form of a packed stream (this library's own wire format, see cdsgd.h)
+// ---------------------------------------------------------------------------
+// A segment is the 256 packed words of one chunk: 8 bitmap words (bit b of word m set iff packed
+// word 32 m + b of the segment is non-zero), then the non-zero words in index order.  Segments
+// sit at a fixed stride of 264 words.
+constexpr unsigned kSegWords = 256;
+constexpr unsigned kSegStride = 8 + kSegWords;
+static_assert(kChunkQuads == 4 * kSegWords, "a segment of the sparse form is the packed stream of one chunk");
+
+// Packed words w0 .. w0+3 (w0 a multiple of 4) of a segment.
+__device__ __forceinline__ u4 sparse_words4(const uint32_t *__restrict__ seg, unsigned w0)
+{
+    const unsigned m = w0 >> 5;
+    unsigned before = 0;  // non-zero words of the segment in front of bitmap word m
+#pragma unroll
+    for (unsigned x = 0; x < 8; ++x)
+        if (x < m) before += (unsigned)__builtin_popcount(seg[x]);
+    const unsigned bm = seg[m];
+    const unsigned bit = w0 & 31u;
+    unsigned pos = 8u + before + (unsigned)__builtin_popcount(bm & ((1u << bit) - 1u));
+    u4 out = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (unsigned i = 0; i < 4; ++i)
+        if ((bm >> (bit + i)) & 1u) out[i] = seg[pos++];
+    return out;
+}
+
+// One workgroup of 256 lanes per segment: lane i owns packed word i.
+__global__ __launch_bounds__(256) void k_sparse_encode(const uint32_t *__restrict__ packed, unsigned long long nw,
+                                                       uint32_t *__restrict__ sparse,
+                                                       uint32_t *__restrict__ seg_words)
+{
+    __shared__ unsigned wave_count[4];
+    const unsigned i = threadIdx.x, wave = i >> 6, lane = i & 63u;
+    const unsigned long long w = (unsigned long long)blockIdx.x * kSegWords + i;
+    const uint32_t v = w < nw ? packed[w] : 0u;
+    const unsigned long long mask = __ballot(v != 0u);  // the wave's 64 words: two bitmap words
+    if (lane == 0) wave_count[wave] = (unsigned)__builtin_popcountll(mask);
+    __syncthreads();
+    unsigned before = 0, total = 0;
+#pragma unroll
+    for (unsigned x = 0; x < 4; ++x) {
+        if (x < wave) before += wave_count[x];
+        total += wave_count[x];
+    }
+    uint32_t *seg = sparse + (size_t)blockIdx.x * kSegStride;
+    if (lane == 0) {
+        seg[2 * wave] = (uint32_t)mask;
+        seg[2 * wave + 1] = (uint32_t)(mask >> 32);
+    }
+    if (v != 0u) seg[8u + before + (unsigned)__builtin_popcountll(mask & ((1ull << lane) - 1ull))] = v;
+    if (i == 0 && seg_words) seg_words[blockIdx.x] = 8u + total;
+}
+
+// a4 on sparse streams, one tensor: 512 lanes per chunk, lane tid takes quads tid and 512 + tid.
+// Four workers at a time are rebuilt into LDS (lane i < 256 rebuilds packed word i of each), then
+// every lane picks its two bytes of each.
+template <bool POW2>
+__global__ __launch_bounds__(512) void k_decode_sum_sparse(StreamTable tab, int num_workers,
+                                                           float *__restrict__ agg_out, Extent ext, float t,
+                                                           float bias_t)
+{
+    __shared__ uint32_t words[4][kSegWords];
+    const unsigned tid = threadIdx.x;
+    const unsigned chunk = blockIdx.x;
+    const bool tail = chunk >= ext.full_chunks;
+    const unsigned rem_elems = tail ? ext.tail_elems : kChunkElems;
+    f4 agg[2] = {f4{0.0f, 0.0f, 0.0f, 0.0f}, f4{0.0f, 0.0f, 0.0f, 0.0f}};
+    unsigned acc[4] = {0u, 0u, 0u, 0u};
+    for (int p0 = 0; p0 < num_workers; p0 += 4) {
+        const int np = num_workers - p0 < 4 ? num_workers - p0 : 4;
+        if (tid < kSegWords) {
+            for (int k = 0; k < np; ++k) {
+                const uint32_t *seg = reinterpret_cast<const uint32_t *>(tab.p[p0 + k]) + (size_t)chunk * kSegStride;
+                const unsigned m = tid >> 5, bit = tid & 31u;
+                const unsigned bm = seg[m];
+                uint32_t v = 0u;
+                if ((bm >> bit) & 1u) {
+                    unsigned before = 0;
+                    for (unsigned x = 0; x < m; ++x) before += (unsigned)__builtin_popcount(seg[x]);
+                    v = seg[8u + before + (unsigned)__builtin_popcount(bm & ((1u << bit) - 1u))];
+                }
+                words[k][tid] = v;
+            }
+        }
+        __syncthreads();
+        for (int k = 0; k < np; ++k) {
+            const uint8_t *bytes = reinterpret_cast<const uint8_t *>(words[k]);
+            const unsigned w = (unsigned)bytes[tid] | ((unsigned)bytes[512u + tid] << 8);
+            if (POW2) {
+                const unsigned z = ((w & 0x55555555u) | 0xAAAAAAAAu) - ((w >> 1) & 0x55555555u);
+                acc[0] += z & 0x03030303u;
+                acc[1] += (z >> 2) & 0x03030303u;
+                acc[2] += (z >> 4) & 0x03030303u;
+                acc[3] += (z >> 6) & 0x03030303u;
+            } else {
+                const unsigned sf = signed_fields(w);
+#pragma unroll
+                for (unsigned j = 0; j < 2; ++j)
+#pragma unroll
+                    for (unsigned c = 0; c < 4; ++c) {
+                        const int mlt = ((int)(sf << (30u - (8u * j + 2u * c)))) >> 30;
+                        agg[j][c] = __builtin_fmaf((float)mlt, t, agg[j][c]);
+                    }
+            }
+        }
+        __syncthreads();
+    }
+    float *out = agg_out + (size_t)chunk * kChunkElems;
+#pragma unroll
+    for (unsigned j = 0; j < 2; ++j) {
+        const unsigned qi = j * 512u + tid;
+        if (POW2) {
+#pragma unroll
+            for (unsigned c = 0; c < 4; ++c)
+                agg[j][c] = __builtin_fmaf((float)((acc[c] >> (8u * j)) & 0xFFu), t, bias_t);
+        }
+        int cnt = (int)rem_elems - (int)(4u * qi);
+        cnt = cnt < 0 ? 0 : (cnt > 4 ? 4 : cnt);
+        if (cnt == 4) st4(out, qi, agg[j]);
+        else st4g<true>(out, qi, cnt, agg[j]);
+    }
+}
+
 // Piece-granular kernels: which piece workgroup b takes.  Workgroup b runs on XCD b % 8.  Within
 // a block of 8 chunks' worth of workgroups, XCD k takes every piece of chunk k, so that the two
 // halves of a 128-byte line of a peer's codes, and the pieces' reads of the chunk's table
@@ -542,29 +680,21 @@ __device__ __forceinline__ unsigned long long piece_of_workgroup(unsigned long l
 // Measured on the VGG-16-shaped list (N = 16, count form): 6.3-6.4 TB/s, where 512-lane
 // workgroups that took a whole chunk, two quads per lane and a byte load per peer, reached
 // 6.0 TB/s; with one wave per piece (64 bytes per peer, half a line) 5.8-6.0 TB/s.
-constexpr unsigned kPieceWaves = CDSGD_PIECE_WAVES;
-constexpr unsigned kPieceQuads = 64 * kPieceWaves;  // lanes per workgroup, one quad each
-constexpr unsigned kCompPiecesPerChunk = kChunkQuads / kPieceQuads;
-static_assert(kChunkQuads % kPieceQuads == 0, "pieces tile a chunk");
+// Waves per piece: four for many workers (two whole lines of every packed stream per workgroup),
+// one for few (N <= 9: the fp32 streams dominate, and they run best in single-wave workgroups).
+constexpr unsigned kPieceWavesMany = CDSGD_PIECE_WAVES;
+constexpr int kFewPeers = CDSGD_FEW_PEERS;
 constexpr unsigned kPeerSlots = 64;  // LDS rows: peers rounded up to a multiple of 16 (63 peers at most)
 static_assert(CDSGD_MAX_WORKERS - 1 <= kPeerSlots, "an LDS row for every peer");
+static_assert(kChunkQuads % (64 * kPieceWavesMany) == 0, "pieces tile a chunk");
 
-typedef unsigned u4 __attribute__((ext_vector_type(4)));
-
-// values of the four codes of a byte, as 2-bit two's-complement fields (01 -> +1, 10 -> -1, else 0)
-__device__ __forceinline__ unsigned signed_fields(unsigned w)
-{
-    const unsigned x = w & 0x55555555u;
-    const unsigned y = (w >> 1) & 0x55555555u;
-    return (x ^ y) | ((y & ~x) << 1);
-}
-
-template <bool G, bool POW2, bool WRITE_LOCAL, int GT>
+template <unsigned kPieceWaves, bool G, bool POW2, bool WRITE_LOCAL, int GT, bool SPARSE>
 __device__ __forceinline__ void fused_piece(const TensorDesc &d, const uint8_t *const *__restrict__ peers,
                                             int num_peers, int self, size_t quad0, unsigned piece,
                                             unsigned rem_elems, unsigned rem_bytes, float t, float lr_local,
                                             float scale, uint8_t *lds)
 {
+    constexpr unsigned kPieceQuads = 64 * kPieceWaves;  // lanes per workgroup, one quad each
     const unsigned lane = threadIdx.x;
     const unsigned qi = piece * kPieceQuads + lane;  // quad of the chunk = byte of the chunk's packed streams
     const void *__restrict__ grad = grad_at<GT>(d.grad, quad0);
@@ -584,7 +714,13 @@ __device__ __forceinline__ void fused_piece(const TensorDesc &d, const uint8_t *
     for (int gI = 0; gI < (int)(kPeerSlots / 16); ++gI) {
         cw[gI] = u4{0u, 0u, 0u, 0u};
         const int p = 16 * gI + (int)(lane / kParts);
-        if (gI < groups && p < num_peers) {
+        if (SPARSE) {
+            // the peer's stream is in the sparse form: rebuild the lane's four packed words from the
+            // segment of this chunk (pad words past the end of the stream have no bit set)
+            if (gI < groups && p < num_peers)
+                cw[gI] = sparse_words4(reinterpret_cast<const uint32_t *>(peers[p]) + (quad0 / kChunkQuads) * kSegStride,
+                                       first >> 2);
+        } else if (gI < groups && p < num_peers) {
             const uint8_t *src = peers[p] + quad0 + first;
             if (!G || first + 16u <= rem_bytes) {
                 typedef unsigned u4a __attribute__((ext_vector_type(4), aligned(4)));
@@ -682,29 +818,33 @@ __device__ __forceinline__ void fused_piece(const TensorDesc &d, const uint8_t *
     }
 }
 
-template <bool POW2, bool WRITE_LOCAL, int GT>
-__global__ __launch_bounds__(64 * CDSGD_PIECE_WAVES) void k_fused_compressed(const TensorDesc *__restrict__ tensors,
-                                                                const ChunkRef *__restrict__ chunks,
-                                                                unsigned long long num_pieces,
-                                                                const uint8_t *const *__restrict__ peers,
-                                                                int num_peers, int self, float t_call,
-                                                                float lr_local, float scale)
+template <unsigned kPieceWaves, bool POW2, bool WRITE_LOCAL, int GT, bool SPARSE>
+__global__ __launch_bounds__(64 * kPieceWaves) void k_fused_compressed(const TensorDesc *__restrict__ tensors,
+                                                                       const ChunkRef *__restrict__ chunks,
+                                                                       unsigned long long num_pieces,
+                                                                       const uint8_t *const *__restrict__ peers,
+                                                                       int num_peers, int self, float t_call,
+                                                                       float lr_local, float scale)
 {
+    constexpr unsigned kPieceQuads = 64 * kPieceWaves;
+    constexpr unsigned kPerChunk = kChunkQuads / kPieceQuads;
     __shared__ __attribute__((aligned(16))) uint8_t lds[kPeerSlots * kPieceQuads];
     for (unsigned long long b = blockIdx.x; b < num_pieces; b += gridDim.x) {
-        const unsigned long long x = piece_of_workgroup<true>(b, kCompPiecesPerChunk, num_pieces);
-        const ChunkRef cr = chunks[x / kCompPiecesPerChunk];
+        const unsigned long long x = piece_of_workgroup<true>(b, kPerChunk, num_pieces);
+        const ChunkRef cr = chunks[x / kPerChunk];
         const TensorDesc d = tensors[cr.tensor];
         const size_t quad0 = (size_t)cr.chunk * kChunkQuads;
-        const unsigned piece = (unsigned)(x % kCompPiecesPerChunk);
+        const unsigned piece = (unsigned)(x % kPerChunk);
         const uint8_t *const *tp = peers + (size_t)cr.tensor * (size_t)num_peers;
         const float t = d.threshold > 0.0f ? d.threshold : t_call;
         if (cr.chunk < d.ext.full_chunks) {
-            fused_piece<false, POW2, WRITE_LOCAL, GT>(d, tp, num_peers, self, quad0, piece, kChunkElems, kChunkQuads, t,
-                                                      lr_local, scale, lds);
-        } else if (piece * kPieceQuads * 4u < d.ext.tail_elems || piece * kPieceQuads < d.ext.tail_bytes) {
-            fused_piece<true, POW2, WRITE_LOCAL, GT>(d, tp, num_peers, self, quad0, piece, d.ext.tail_elems,
-                                                     d.ext.tail_bytes, t, lr_local, scale, lds);
+            fused_piece<kPieceWaves, false, POW2, WRITE_LOCAL, GT, SPARSE>(d, tp, num_peers, self, quad0, piece, kChunkElems,
+                                                                   kChunkQuads, t, lr_local, scale, lds);
+        } else if (piece * kPieceQuads < d.ext.tail_bytes) {
+            // (the packed bytes of the ragged end cover its elements: pieces past them have nothing to do)
+            fused_piece<kPieceWaves, true, POW2, WRITE_LOCAL, GT, SPARSE>(d, tp, num_peers, self, quad0, piece,
+                                                                  d.ext.tail_elems, d.ext.tail_bytes, t, lr_local,
+                                                                  scale, lds);
         }
     }
 }
@@ -936,6 +1076,7 @@ struct PlanTables {
     bool own_thresholds = false;       // every tensor carries its own threshold
     bool own_thresholds_pow2 = false;  // ... and all of them are powers of two
     unsigned max_workgroups = 0;       // > 0: launch at most this many workgroups (they take several chunks each)
+    bool peers_sparse = false;         // the peers' streams are in the sparse form (cdsgd_plan_set_peer_format)
 
     // Workgroups to launch for `units` units of work (chunks, or pieces of chunks).
     unsigned grid_size(unsigned long long units) const
@@ -1277,11 +1418,22 @@ int launch_formal_pass(const PlanTables *plan, long step, int k, float threshold
     const float scale = lr_global / (float)plan->num_workers;
     hipStream_t s = (hipStream_t)hip_stream;
     const int num_peers = plan->num_workers - 1;
-    const unsigned long long num_pieces = (unsigned long long)plan->num_chunks * kCompPiecesPerChunk;
-    const dim3 grid(plan->grid_size(num_pieces)), block(kPieceQuads);
-#define CDSGD_LAUNCH_COMPRESSED_T(POW2, LOCAL, GT)                                                            \
-    hipLaunchKernelGGL((k_fused_compressed<POW2, LOCAL, GT>), grid, block, 0, s, plan->tensors,                \
+    const unsigned waves = num_peers <= kFewPeers ? 1u : kPieceWavesMany;
+    const unsigned long long num_pieces = (unsigned long long)plan->num_chunks * (kChunkQuads / (64u * waves));
+    const dim3 grid(plan->grid_size(num_pieces)), block(64u * waves);
+#define CDSGD_LAUNCH_COMPRESSED_S(W, POW2, LOCAL, GT, SPARSE)                                                  \
+    hipLaunchKernelGGL((k_fused_compressed<W, POW2, LOCAL, GT, SPARSE>), grid, block, 0, s, plan->tensors,      \
                        plan->chunks, num_pieces, plan->peers, num_peers, plan->self, threshold, lr_local, scale)
+#define CDSGD_LAUNCH_COMPRESSED_W(W, POW2, LOCAL, GT)                                                          \
+    do {                                                                                                       \
+        if (plan->peers_sparse) CDSGD_LAUNCH_COMPRESSED_S(W, POW2, LOCAL, GT, true);                            \
+        else CDSGD_LAUNCH_COMPRESSED_S(W, POW2, LOCAL, GT, false);                                              \
+    } while (0)
+#define CDSGD_LAUNCH_COMPRESSED_T(POW2, LOCAL, GT)                                                            \
+    do {                                                                                                       \
+        if (waves == 1u) CDSGD_LAUNCH_COMPRESSED_W(1u, POW2, LOCAL, GT);                                        \
+        else CDSGD_LAUNCH_COMPRESSED_W(kPieceWavesMany, POW2, LOCAL, GT);                                       \
+    } while (0)
 #define CDSGD_LAUNCH_COMPRESSED(POW2, LOCAL)                                                                  \
     do {                                                                                                       \
         if (plan->grad_type == kGradBF16) CDSGD_LAUNCH_COMPRESSED_T(POW2, LOCAL, kGradBF16);                   \
@@ -1299,6 +1451,8 @@ int launch_formal_pass(const PlanTables *plan, long step, int k, float threshold
     }
 #undef CDSGD_LAUNCH_COMPRESSED
 #undef CDSGD_LAUNCH_COMPRESSED_T
+#undef CDSGD_LAUNCH_COMPRESSED_W
+#undef CDSGD_LAUNCH_COMPRESSED_S
     return launch_status();
 }
 
@@ -1384,6 +1538,61 @@ int cdsgd_plan_set_thresholds(cdsgd_plan *plan, const float *thresholds)
     plan->host_tensors.swap(next);
     plan->own_thresholds = thresholds != nullptr;
     plan->own_thresholds_pow2 = thresholds != nullptr && all_pow2;
+    return CDSGD_OK;
+}
+
+size_t cdsgd_sparse_segments(size_t n) { return ((n + 15) / 16 + kSegWords - 1) / kSegWords; }
+
+size_t cdsgd_sparse_words(size_t n) { return cdsgd_sparse_segments(n) * kSegStride; }
+
+int cdsgd_sparse_encode(const uint32_t *packed, size_t n, uint32_t *sparse, uint32_t *segment_words,
+                        void *hip_stream)
+{
+    if (!packed || !sparse) return CDSGD_ERR_NULL;
+    if (n == 0 || cdsgd_sparse_segments(n) > kMaxGrid) return CDSGD_ERR_SIZE;
+    if (!aligned(packed, 4) || !aligned(sparse, 4) || !aligned(segment_words, 4)) return CDSGD_ERR_ALIGN;
+    const size_t pb = (size_t)packed_bytes_of(n), sb = cdsgd_sparse_words(n) * 4, cb = cdsgd_sparse_segments(n) * 4;
+    if (overlap2(packed, pb, sparse, sb) || overlap2(packed, pb, segment_words, cb) ||
+        overlap2(sparse, sb, segment_words, cb))
+        return CDSGD_ERR_ALIAS;
+    hipLaunchKernelGGL(k_sparse_encode, dim3((unsigned)cdsgd_sparse_segments(n)), dim3(256), 0,
+                       (hipStream_t)hip_stream, packed, (unsigned long long)((n + 15) / 16), sparse, segment_words);
+    return launch_status();
+}
+
+int cdsgd_decode_sum_sparse(const uint32_t *const *sparse, int num_workers, float *agg, size_t n, float threshold,
+                            void *hip_stream)
+{
+    if (!sparse || !agg) return CDSGD_ERR_NULL;
+    if (n == 0 || chunks_of(n) > kMaxGrid) return CDSGD_ERR_SIZE;
+    if (!good_threshold(threshold)) return CDSGD_ERR_PARAM;
+    if (num_workers < 1 || num_workers > CDSGD_MAX_WORKERS) return CDSGD_ERR_WORKERS;
+    for (int j = 0; j < num_workers; ++j)
+        if (!sparse[j]) return CDSGD_ERR_NULL;
+    if (!aligned(agg, 16)) return CDSGD_ERR_ALIGN;
+    for (int j = 0; j < num_workers; ++j)
+        if (!aligned(sparse[j], 4)) return CDSGD_ERR_ALIGN;
+    for (int j = 0; j < num_workers; ++j)
+        if (overlap2(sparse[j], cdsgd_sparse_words(n) * 4, agg, n * sizeof(float))) return CDSGD_ERR_ALIAS;
+    StreamTable tab;
+    std::memset(&tab, 0, sizeof(tab));
+    for (int j = 0; j < num_workers; ++j) tab.p[j] = reinterpret_cast<const uint8_t *>(sparse[j]);
+    const unsigned grid = (unsigned)chunks_of(n);
+    const float bias_t = -(2.0f * (float)num_workers) * threshold;
+    if (is_pow2_threshold(threshold))
+        hipLaunchKernelGGL(k_decode_sum_sparse<true>, dim3(grid), dim3(512), 0, (hipStream_t)hip_stream, tab,
+                           num_workers, agg, extent_of(n), threshold, bias_t);
+    else
+        hipLaunchKernelGGL(k_decode_sum_sparse<false>, dim3(grid), dim3(512), 0, (hipStream_t)hip_stream, tab,
+                           num_workers, agg, extent_of(n), threshold, bias_t);
+    return launch_status();
+}
+
+int cdsgd_plan_set_peer_format(cdsgd_plan *plan, int format)
+{
+    if (!plan) return CDSGD_ERR_NULL;
+    if (format != CDSGD_PEERS_PACKED && format != CDSGD_PEERS_SPARSE) return CDSGD_ERR_PARAM;
+    plan->peers_sparse = format == CDSGD_PEERS_SPARSE;
     return CDSGD_OK;
 }
 

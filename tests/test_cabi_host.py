@@ -32,7 +32,8 @@ def test_header_declares_the_named_entry_points():
                  "cdsgd_trainer_step", "cdsgd_trainer_iteration", "cdsgd_trainer_destroy",
                  "cdsgd_step_local", "cdsgd_step_global", "cdsgd_cost_iteration", "cdsgd_cost_period_mean",
                  "cdsgd_plan_create_typed", "cdsgd_plan_set_thresholds", "cdsgd_plan_set_max_workgroups",
-                 "cdsgd_step_fused_static", "cdsgd_build_id"):
+                 "cdsgd_step_fused_static", "cdsgd_build_id", "cdsgd_sparse_encode", "cdsgd_decode_sum_sparse",
+                 "cdsgd_sparse_words", "cdsgd_sparse_segments", "cdsgd_plan_set_peer_format"):
         assert must in names
 
 
@@ -62,6 +63,29 @@ def test_library_matches_the_tree(L, monkeypatch):
 def test_packed_words(L):
     for n, w in ((1, 1), (15, 1), (16, 1), (17, 2), (32, 2), (33, 3), (65536, 4096), (1 << 30, 1 << 26)):
         assert L.cdsgd_packed_words(n) == w
+
+
+def test_sparse_sizes_and_argument_errors(L):
+    from paper_2106_10796_amd.binding import ERR_ALIAS, ERR_ALIGN, ERR_NULL, ERR_PARAM, ERR_SIZE, ERR_WORKERS
+    for n, segs in ((1, 1), (4096, 1), (4097, 2), (8192, 2), (8193, 3), (1 << 30, 1 << 18)):
+        assert L.cdsgd_sparse_segments(n) == segs and L.cdsgd_sparse_words(n) == 264 * segs
+    e = L.cdsgd_sparse_encode
+    assert e(None, 16, A, None, None) == ERR_NULL
+    assert e(A, 16, None, None, None) == ERR_NULL
+    assert e(A, 0, A + 0x10000, None, None) == ERR_SIZE
+    assert e(A + 2, 16, A + 0x10000, None, None) == ERR_ALIGN
+    assert e(A, 16, A, None, None) == ERR_ALIAS
+    assert e(A, 4096 * 4, A + 1024, None, None) == ERR_ALIAS        # sparse buffer inside the packed stream
+    d = L.cdsgd_decode_sum_sparse
+    two = (ctypes.c_void_p * 2)(A, A + 0x10000)
+    assert d(None, 2, A + 0x20000, 16, 0.5, None) == ERR_NULL
+    assert d(two, 2, None, 16, 0.5, None) == ERR_NULL
+    assert d(two, 2, A + 0x20000, 0, 0.5, None) == ERR_SIZE
+    assert d(two, 2, A + 0x20000, 16, 0.0, None) == ERR_PARAM
+    assert d(two, 65, A + 0x20000, 16, 0.5, None) == ERR_WORKERS
+    assert d(two, 2, A + 0x20004, 16, 0.5, None) == ERR_ALIGN
+    assert d(two, 2, A + 64, 16, 0.5, None) == ERR_ALIAS
+    assert L.cdsgd_plan_set_peer_format(None, 0) == ERR_NULL
 
 
 def test_status_strings(L):

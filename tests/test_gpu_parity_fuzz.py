@@ -1,7 +1,8 @@
 """Seeded random configurations of Alg. 1 end to end through cdsgd_trainer_step: layer lists,
 worker counts and positions, periods, warm-up lengths, thresholds (one per call or one per
-tensor, both decode forms), gradient types (fp32, bf16, fp16) and both sources of the 32-bit
-aggregate -- every iteration compared with the oracle's trainer bit for bit.
+tensor, both decode forms), gradient types (fp32, bf16, fp16), both sources of the 32-bit
+aggregate, peers' streams packed or in the sparse form, bounded grids -- every iteration
+compared with the oracle's trainer bit for bit.
 CDSGD_FUZZ_CASES raises the number of cases for a longer soak; CDSGD_FUZZ_SEED moves the stream."""
 import os
 
@@ -56,7 +57,8 @@ def draw_case(rng):
     return dict(sizes=sizes, N=N, self_rank=int(rng.integers(0, N)), k=int(rng.integers(1, 5)),
                 warmup_n=int(rng.integers(0, 4)), t=float(rng.choice(pool)), thresholds=thresholds,
                 dtype=str(rng.choice(["float32", "float32", "bfloat16", "float16"])),
-                full_grads=bool(rng.integers(0, 2)), formal=int(rng.integers(2, 7)))
+                full_grads=bool(rng.integers(0, 2)), formal=int(rng.integers(2, 7)),
+                sparse_peers=bool(rng.integers(0, 3) == 0), max_workgroups=int(rng.choice([0, 0, 0, 1, 3, 50])))
 
 
 def run_case(B, oracle, c, seed):
@@ -74,10 +76,13 @@ def run_case(B, oracle, c, seed):
               grad=[torch.zeros(n, dtype=gd, **dev) for n in sizes],
               packed_self=[torch.full((B.packed_words(n),), -1, dtype=torch.int32, **dev) for n in sizes],
               agg_full=[torch.zeros(n, **dev) for n in sizes])
-    peers = [None if j == self_rank else [B.new_packed(n) for n in sizes] for j in range(N)]
+    sparse = c["sparse_peers"]
+    peers = [None if j == self_rank else [(B.new_sparse(n) if sparse else B.new_packed(n)) for n in sizes]
+             for j in range(N)]
     peer_g = [None if j == self_rank else [torch.zeros(n, dtype=gd, **dev) for n in sizes] for j in range(N)]
     plan = B.Plan([{key: st[key][i] for key in st} for i in range(T)], peers if N > 1 else None, N, self_rank,
-                  grad_dtype=gd)
+                  grad_dtype=gd, peers_sparse=sparse)
+    plan.set_max_workgroups(c["max_workgroups"])
     if c["full_grads"]:
         plan.bind_full_grads(peer_g)
     if c["thresholds"]:
@@ -96,7 +101,8 @@ def run_case(B, oracle, c, seed):
                 if j == self_rank:
                     continue
                 if mode == 1:
-                    peers[j][i].copy_(torch.from_numpy(words[j].view(np.int32)))
+                    wire = oracle.sparse_encode(words[j], n, fill=0x11111111)[0] if sparse else words[j]
+                    peers[j][i].copy_(torch.from_numpy(wire.view(np.int32)))
                 elif c["full_grads"]:
                     peer_g[j][i].copy_(torch.from_numpy(grads[j]).to(gd))
             if mode != 1 and not c["full_grads"]:
