@@ -84,12 +84,12 @@ def timed_blocks(run_block, steps, stream, min_seconds=MIN_TIMED_SECONDS, min_bl
 
 
 def time_workload(name, steps, warmup, want_correction=True, want_unfused=False, grad_dtype=None,
-                  min_seconds=MIN_TIMED_SECONDS):
+                  min_seconds=MIN_TIMED_SECONDS, sparse_peers=False, dense=False):
     import torch
     from paper_2106_10796_amd import runner, synth
     cfg = synth.config(name)
     _progress("%s: building the workload and the peers' streams" % name)
-    wl = runner.Workload(cfg, grad_dtype=grad_dtype or torch.float32)
+    wl = runner.Workload(cfg, grad_dtype=grad_dtype or torch.float32, sparse_peers=sparse_peers, dense=dense)
     grad_bytes = 4 if grad_dtype in (None, torch.float32) else 2
     # inputs of a compressed step (own gradient, the peers' packed streams) and of a correction step
     if want_correction:
@@ -556,6 +556,31 @@ def main():
         del w
         torch.cuda.empty_cache()
         extra["bf16_gradients_" + args.workload] = r
+        # the peers' streams in the sparse wire form (the library's own format, beyond the paper): on the
+        # literal recipe nothing fires, so a peer costs 32 bytes of bitmap per chunk instead of 1 KiB; on the
+        # dense parity recipe (a third of the codes fire) nearly every word travels.  GB/s here uses the
+        # bytes this form really moves per element, stated next to the rate.
+        for tag, dense in (("literal", False), ("dense", True)):
+            r, w = time_workload(args.workload, max(5, args.steps // 2), max(2, args.warmup // 2),
+                                 want_correction=False, min_seconds=0.5, sparse_peers=True, dense=dense)
+            n_el, N = r["elements"], r["num_workers"]
+            peer_bytes = 0.0
+            for j in range(N):
+                if w.peer_sparse[j] is not None:
+                    for i, n in enumerate(w.cfg.sizes):
+                        sv = w.sview(w.peer_sparse[j], i).view(-1, 264)[:, :8]
+                        bits = sv.to(torch.int64) & 0xFFFFFFFF
+                        nz = sum(int(((bits >> b) & 1).sum().item()) for b in range(32))
+                        peer_bytes += 4.0 * (8 * sv.shape[0] + nz)
+            bpe = 24.25 + peer_bytes / n_el
+            r["bytes_per_element_sparse"] = bpe
+            r["gbs_sparse_bytes"] = n_el * bpe / (r["ms_per_step"] * 1e-3) / 1e9
+            r["note"] = "ms_per_step is the figure to compare with the packed form; gbs / frac_hbm_peak in this " \
+                        "entry are still computed with the packed form's 24 + N/4 bytes"
+            w.destroy()
+            del w
+            torch.cuda.empty_cache()
+            extra["sparse_peers_%s_%s" % (tag, args.workload)] = r
         # the paper's time model (Sec. 3.3) fed with the measured delta; tau and the wire are assumptions
         n_el, k = head["elements"], head["k"]
         wire = 56e9 / 8                                   # the paper's 56 Gbps InfiniBand, bytes/s

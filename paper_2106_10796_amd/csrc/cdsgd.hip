@@ -530,21 +530,33 @@ constexpr unsigned kSegWords = 256;
 constexpr unsigned kSegStride = 8 + kSegWords;
 static_assert(kChunkQuads == 4 * kSegWords, "a segment of the sparse form is the packed stream of one chunk");
 
-// Packed words w0 .. w0+3 (w0 a multiple of 4) of a segment.
-__device__ __forceinline__ u4 sparse_words4(const uint32_t *__restrict__ seg, unsigned w0)
+// Packed words w0 .. w0+3 (w0 a multiple of 4) of a segment whose 8 bitmap words are in `bitmap`
+// (LDS).  The non-zero ones among them lie next to each other behind the bitmap, so one 128-bit
+// load fetches them (it may run into slots behind the segment's last value, never past its 264
+// words); the bitmap says which of the four each loaded word is.
+__device__ __forceinline__ u4 sparse_words4(const uint32_t *__restrict__ seg, const uint32_t *bitmap, unsigned w0)
 {
     const unsigned m = w0 >> 5;
     unsigned before = 0;  // non-zero words of the segment in front of bitmap word m
 #pragma unroll
     for (unsigned x = 0; x < 8; ++x)
-        if (x < m) before += (unsigned)__builtin_popcount(seg[x]);
-    const unsigned bm = seg[m];
+        if (x < m) before += (unsigned)__builtin_popcount(bitmap[x]);
+    const unsigned bm = bitmap[m];
     const unsigned bit = w0 & 31u;
-    unsigned pos = 8u + before + (unsigned)__builtin_popcount(bm & ((1u << bit) - 1u));
+    const unsigned four = (bm >> bit) & 15u;
     u4 out = {0u, 0u, 0u, 0u};
+    if (four != 0u) {
+        typedef unsigned u4a __attribute__((ext_vector_type(4), aligned(4)));
+        const unsigned pos = 8u + before + (unsigned)__builtin_popcount(bm & ((1u << bit) - 1u));
+        const u4 v = *reinterpret_cast<const u4a *>(seg + pos);
+        unsigned rank = 0;
 #pragma unroll
-    for (unsigned i = 0; i < 4; ++i)
-        if ((bm >> (bit + i)) & 1u) out[i] = seg[pos++];
+        for (unsigned i = 0; i < 4; ++i)
+            if ((four >> i) & 1u) {
+                out[i] = rank == 0 ? v[0] : (rank == 1 ? v[1] : (rank == 2 ? v[2] : v[3]));
+                ++rank;
+            }
+    }
     return out;
 }
 
@@ -709,6 +721,23 @@ __device__ __forceinline__ void fused_piece(const TensorDesc &d, const uint8_t *
     const unsigned part = lane % kParts;                 // which of them this lane fetches
     const unsigned first = piece * kPieceQuads + 16u * part;  // its first byte within the chunk
     const int groups = (num_peers + 15) >> 4;
+    uint32_t *bitmaps = reinterpret_cast<uint32_t *>(lds + kPeerSlots * kPieceQuads);  // [peer][8], sparse form only
+    if (SPARSE) {
+        // the segments' bitmaps first (8 words per peer, one word per lane), through LDS to every lane
+        for (unsigned e = lane; e < 8u * 16u * (unsigned)groups; e += kPieceQuads) {
+            const int p = (int)(e >> 3);
+            bitmaps[e] = p < num_peers ? (reinterpret_cast<const uint32_t *>(peers[p]) +
+                                          (quad0 / kChunkQuads) * kSegStride)[e & 7u]
+                                       : 0u;
+        }
+        if (kPieceWaves == 1) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        } else {
+            __syncthreads();
+        }
+    }
     u4 cw[kPeerSlots / 16];
 #pragma unroll
     for (int gI = 0; gI < (int)(kPeerSlots / 16); ++gI) {
@@ -719,7 +748,7 @@ __device__ __forceinline__ void fused_piece(const TensorDesc &d, const uint8_t *
             // segment of this chunk (pad words past the end of the stream have no bit set)
             if (gI < groups && p < num_peers)
                 cw[gI] = sparse_words4(reinterpret_cast<const uint32_t *>(peers[p]) + (quad0 / kChunkQuads) * kSegStride,
-                                       first >> 2);
+                                       bitmaps + (16u * gI + lane / kParts) * 8u, first >> 2);
         } else if (gI < groups && p < num_peers) {
             const uint8_t *src = peers[p] + quad0 + first;
             if (!G || first + 16u <= rem_bytes) {
@@ -828,7 +857,7 @@ __global__ __launch_bounds__(64 * kPieceWaves) void k_fused_compressed(const Ten
 {
     constexpr unsigned kPieceQuads = 64 * kPieceWaves;
     constexpr unsigned kPerChunk = kChunkQuads / kPieceQuads;
-    __shared__ __attribute__((aligned(16))) uint8_t lds[kPeerSlots * kPieceQuads];
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kPeerSlots * kPieceQuads + (SPARSE ? kPeerSlots * 32 : 0)];
     for (unsigned long long b = blockIdx.x; b < num_pieces; b += gridDim.x) {
         const unsigned long long x = piece_of_workgroup<true>(b, kPerChunk, num_pieces);
         const ChunkRef cr = chunks[x / kPerChunk];

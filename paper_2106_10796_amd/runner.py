@@ -33,7 +33,8 @@ arena_allocator = default_arena
 
 class Workload:
     def __init__(self, cfg: synth.Config, device="cuda", dense: bool = False, self_rank: int = 0,
-                 peer_residuals: bool = True, full_grads: bool = False, grad_dtype=torch.float32):
+                 peer_residuals: bool = True, full_grads: bool = False, grad_dtype=torch.float32,
+                 sparse_peers: bool = False):
         self.cfg = cfg
         self.device = torch.device(device)
         self.dense = dense
@@ -63,6 +64,17 @@ class Workload:
         self.peer_residual: List[Optional[torch.Tensor]] = [
             None if (j == self.self_rank or not peer_residuals) else torch.zeros(self.total, **f32)
             for j in range(self.N)]
+        # sparse_peers: the observed worker reads the peers' streams in the library's sparse form; every
+        # peer's packed stream (made by cdsgd_quantize_pack as before) is re-encoded tensor by tensor
+        self.sparse_peers = sparse_peers
+        self.soff: List[int] = []
+        so = 0
+        for n in cfg.sizes:
+            self.soff.append(so)
+            so += binding.sparse_words(n) if sparse_peers else 0
+        self.peer_sparse: List[Optional[torch.Tensor]] = [
+            None if (j == self.self_rank or not sparse_peers) else alloc(so, binding.PACKED_DTYPE, self.device)
+            for j in range(self.N)]
         self._scratch = torch.zeros(self.total, **f32)   # a peer's gradient, one worker at a time
         # full_grads: every peer's 32-bit gradient stays resident (what the server side would hold on a
         # correction or warm-up pass) and those passes sum in the kernel instead of reading agg_full
@@ -76,7 +88,7 @@ class Workload:
         self.w_local.copy_(self.w_global)
         self.thresholds = None
         self.plan = binding.Plan(self._plan_tensors(), self._plan_peers(), self.N, self.self_rank,
-                                 grad_dtype=grad_dtype)
+                                 grad_dtype=grad_dtype, peers_sparse=sparse_peers)
         if full_grads and self.N > 1:
             self.plan.bind_full_grads([None if j == self.self_rank else
                                        [self.view(self.peer_grad[j], i) for i in range(cfg.num_tensors)]
@@ -101,9 +113,16 @@ class Workload:
                      packed_self=self.pview(self.packed_self, i), agg_full=self.view(self.agg_full, i))
                 for i in range(self.cfg.num_tensors)]
 
+    def sview(self, arena: torch.Tensor, i: int) -> torch.Tensor:
+        return arena[self.soff[i]: self.soff[i] + binding.sparse_words(self.cfg.sizes[i])]
+
     def _plan_peers(self):
         if self.N == 1:
             return None
+        if self.sparse_peers:
+            return [None if j == self.self_rank else [self.sview(self.peer_sparse[j], i)
+                                                      for i in range(self.cfg.num_tensors)]
+                    for j in range(self.N)]
         return [None if j == self.self_rank else [self.pview(self.peer_packed[j], i)
                                                   for i in range(self.cfg.num_tensors)]
                 for j in range(self.N)]
@@ -157,6 +176,10 @@ class Workload:
                         for i in range(self.cfg.num_tensors):
                             binding.cdsgd_quantize_pack(self.view(g, i), self.view(self.peer_residual[j], i),
                                                         self.pview(self.peer_packed[j], i), self.thresholds[i])
+                    if self.sparse_peers:
+                        for i, n in enumerate(self.cfg.sizes):
+                            binding.cdsgd_sparse_encode(self.pview(self.peer_packed[j], i), n,
+                                                        self.sview(self.peer_sparse[j], i))
             if not comp:
                 self.agg_full.add_(g)   # worker order 0..N-1, fp32, from +0
             if capture is not None:
