@@ -11,8 +11,9 @@
 //     lane: 256-lane workgroups for the compressed pass (the peers' codes
 //     come in through LDS, 128 bits per lane and 16 peers per instruction),
 //     single waves for the passes on 32-bit gradients.
-//   * The single-tensor kernels give a chunk to a workgroup of kBlock lanes,
-//     lane `tid` taking quads j*kBlock + tid.
+//   * Of the single-tensor kernels, decode-and-sum and the update give a chunk
+//     to a workgroup of kBlock lanes, lane `tid` taking quads j*kBlock + tid;
+//     quantise-and-pack works in single-wave pieces.
 // Either way every wave instruction on an fp32 buffer touches one contiguous
 // 1 KiB span: all traffic is fully coalesced.
 //
@@ -31,11 +32,11 @@
 
 #include "cdsgd.h"
 
-// Launch shape and cache policy, chosen by measurement on MI355X (sweeps over
-// 64..1024 lanes, 1..4 quads per lane, 4..16 streams in flight): all shapes
-// land within run-to-run noise of each other once the non-temporal policy is
-// on; non-temporal loads and stores are worth about 15 % (every byte is touched
-// once per step, so nothing should stay in L2 or the memory-side cache).
+// Launch shapes and cache policy are chosen by measurement on MI355X; each kernel
+// states its own.  CDSGD_BLOCK x CDSGD_QPL is the shape of the chunk-per-workgroup
+// kernels (k_decode_sum, k_update) and fixes the chunk size of the plan tables.
+// Non-temporal loads and stores are worth about 15 % (every byte is touched once
+// per step, so nothing should stay in L2 or the memory-side cache).
 #ifndef CDSGD_BLOCK
 #define CDSGD_BLOCK 512
 #endif
@@ -376,47 +377,6 @@ struct ChunkRef {
 // kernels
 // ---------------------------------------------------------------------------
 
-// a1-a3 for one tensor.
-template <bool G>
-__device__ __forceinline__ void quantize_pack_chunk(const float *__restrict__ grad,
-                                                    float *__restrict__ resid,
-                                                    uint8_t *__restrict__ packed, unsigned rem_elems,
-                                                    unsigned rem_bytes, float t)
-{
-    const unsigned tid = threadIdx.x;
-    f4 g[kQpl], r[kQpl];
-    int cnt[kQpl];
-#pragma unroll
-    for (unsigned j = 0; j < kQpl; ++j) {
-        const unsigned qi = j * kBlock + tid;
-        cnt[j] = quad_count<G>(rem_elems, qi);
-        g[j] = ld4g<G>(grad, qi, cnt[j]);
-        r[j] = ld4g<G>(resid, qi, cnt[j]);
-    }
-#pragma unroll
-    for (unsigned j = 0; j < kQpl; ++j) {
-        const unsigned qi = j * kBlock + tid;
-        f4 sent;
-        const unsigned b = quantize_quad(g[j], r[j], t, sent);
-        st4g<G>(resid, qi, cnt[j], r[j]);
-        if (!G || qi < rem_bytes) packed[qi] = (uint8_t)b;
-    }
-}
-
-__global__ __launch_bounds__(CDSGD_BLOCK) void k_quantize_pack(const float *__restrict__ grad,
-                                                               float *__restrict__ resid,
-                                                               uint8_t *__restrict__ packed, Extent ext,
-                                                               float t)
-{
-    const unsigned chunk = blockIdx.x;
-    const size_t quad0 = (size_t)chunk * kChunkQuads;
-    grad += 4 * quad0;
-    resid += 4 * quad0;
-    packed += quad0;
-    if (chunk < ext.full_chunks) quantize_pack_chunk<false>(grad, resid, packed, kChunkElems, kChunkQuads, t);
-    else quantize_pack_chunk<true>(grad, resid, packed, ext.tail_elems, ext.tail_bytes, t);
-}
-
 // a4 for one tensor; the worker pointers travel in the kernel arguments.
 struct StreamTable {
     const uint8_t *p[CDSGD_MAX_WORKERS];
@@ -654,6 +614,36 @@ __global__ __launch_bounds__(512) void k_decode_sum_sparse(StreamTable tab, int 
         cnt = cnt < 0 ? 0 : (cnt > 4 ? 4 : cnt);
         if (cnt == 4) st4(out, qi, agg[j]);
         else st4g<true>(out, qi, cnt, agg[j]);
+    }
+}
+
+// a1-a3 for one tensor, one wave per piece of L = 64 quads (measured: 6.68 TB/s against 6.41 TB/s for
+// 512-lane workgroups with two quads per lane; the other two single-tensor kernels are faster in that
+// shape and keep it).  `ext` describes the tensor in pieces: full_chunks whole pieces, then at most one
+// ragged piece of tail_elems elements and tail_bytes packed bytes.
+template <unsigned L>
+__global__ __launch_bounds__(L) void k_quantize_pack(const float *__restrict__ grad, float *__restrict__ resid,
+                                                       uint8_t *__restrict__ packed, Extent ext, float t)
+{
+    const unsigned piece = blockIdx.x, lane = threadIdx.x;
+    const size_t quad0 = (size_t)piece * L;
+    grad += 4 * quad0;
+    resid += 4 * quad0;
+    packed += quad0;
+    f4 sent;
+    if (piece < ext.full_chunks) {
+        const f4 g = ld4(grad, lane);
+        f4 r = ld4(resid, lane);
+        const unsigned b = quantize_quad(g, r, t, sent);
+        st4(resid, lane, r);
+        packed[lane] = (uint8_t)b;
+    } else {
+        const int cnt = quad_count<true>(ext.tail_elems, lane);
+        const f4 g = ld4g<true>(grad, lane, cnt);
+        f4 r = ld4g<true>(resid, lane, cnt);
+        const unsigned b = quantize_quad(g, r, t, sent);
+        st4g<true>(resid, lane, cnt, r);
+        if (lane < ext.tail_bytes) packed[lane] = (uint8_t)b;
     }
 }
 
@@ -1064,7 +1054,25 @@ inline Extent extent_of(size_t n)
     return e;
 }
 
+// The same in units of `unit_quads` quads (the single-tensor kernels' pieces).
+inline unsigned long long units_of(size_t n, unsigned unit_quads)
+{
+    return (packed_bytes_of(n) + unit_quads - 1) / unit_quads;
+}
+
+inline Extent extent_of_units(size_t n, unsigned unit_quads)
+{
+    Extent e;
+    const unsigned long long full = n / (4ull * unit_quads);
+    e.full_chunks = (unsigned)full;
+    e.tail_elems = (unsigned)(n - full * 4ull * unit_quads);
+    e.tail_bytes = (unsigned)(packed_bytes_of(n) - full * unit_quads);
+    e.pad_ = 0;
+    return e;
+}
+
 constexpr unsigned long long kMaxGrid = 0x7FFFFFFFull;
+constexpr unsigned kQuantLanes = 64;  // lanes = quads of a piece of k_quantize_pack
 
 // A threshold 2^e (moderate e): every multiple m*t, |m| <= 2*CDSGD_MAX_WORKERS, is exact.
 inline bool is_pow2_threshold(float t)
@@ -1272,16 +1280,16 @@ int cdsgd_quantize_pack(const float *grad, float *residual, uint32_t *packed, si
                         void *hip_stream)
 {
     if (!grad || !residual || !packed) return CDSGD_ERR_NULL;
-    if (n == 0 || chunks_of(n) > kMaxGrid) return CDSGD_ERR_SIZE;
+    if (n == 0 || units_of(n, kQuantLanes) > kMaxGrid) return CDSGD_ERR_SIZE;
     if (!good_threshold(threshold)) return CDSGD_ERR_PARAM;
     if (!aligned(grad, 16) || !aligned(residual, 16) || !aligned(packed, 4)) return CDSGD_ERR_ALIGN;
     if (overlap(grad, residual, n * sizeof(float)) ||
         overlap2(packed, (size_t)packed_bytes_of(n), grad, n * sizeof(float)) ||
         overlap2(packed, (size_t)packed_bytes_of(n), residual, n * sizeof(float)))
         return CDSGD_ERR_ALIAS;
-    const unsigned grid = (unsigned)chunks_of(n);
-    hipLaunchKernelGGL(k_quantize_pack, dim3(grid), dim3(kBlock), 0, (hipStream_t)hip_stream, grad, residual,
-                       reinterpret_cast<uint8_t *>(packed), extent_of(n), threshold);
+    hipLaunchKernelGGL(k_quantize_pack<kQuantLanes>, dim3((unsigned)units_of(n, kQuantLanes)), dim3(kQuantLanes), 0,
+                       (hipStream_t)hip_stream, grad, residual, reinterpret_cast<uint8_t *>(packed),
+                       extent_of_units(n, kQuantLanes), threshold);
     return launch_status();
 }
 
@@ -1302,8 +1310,8 @@ int cdsgd_decode_sum(const uint32_t *const *packed, int num_workers, float *agg,
     StreamTable tab;
     std::memset(&tab, 0, sizeof(tab));
     for (int j = 0; j < num_workers; ++j) tab.p[j] = reinterpret_cast<const uint8_t *>(packed[j]);
-    const unsigned grid = (unsigned)chunks_of(n);
     const float bias_t = -(2.0f * (float)num_workers) * threshold;
+    const unsigned grid = (unsigned)chunks_of(n);
     if (is_pow2_threshold(threshold))
         hipLaunchKernelGGL(k_decode_sum<true>, dim3(grid), dim3(kBlock), 0, (hipStream_t)hip_stream, tab,
                            num_workers, agg, extent_of(n), threshold, bias_t);
@@ -1330,9 +1338,9 @@ int cdsgd_update(float *w_global, float *w_local, const float *grad_local, const
         overlap(w_local, agg, n * sizeof(float)) || overlap(w_global, grad_local, n * sizeof(float)) ||
         overlap(w_global, agg, n * sizeof(float)))
         return CDSGD_ERR_ALIAS;
-    const unsigned grid = (unsigned)chunks_of(n);
     const float scale = lr_global / (float)num_workers;
     hipStream_t s = (hipStream_t)hip_stream;
+    const unsigned grid = (unsigned)chunks_of(n);
     const Extent nn = extent_of(n);
     if (local && global)
         hipLaunchKernelGGL((k_update<true, true>), dim3(grid), dim3(kBlock), 0, s, w_global, w_local, grad_local, agg, nn, lr_local, scale);
