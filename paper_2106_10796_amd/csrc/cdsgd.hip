@@ -364,14 +364,11 @@ struct ChunkRef {
     unsigned chunk;   // chunk number inside that tensor
 };
 
-// Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b % 8), so
-// consecutive chunks run on different XCDs; a streaming pass has no reuse for an XCD's L2 to
-// exploit, and giving each XCD a contiguous eighth of the chunk list measured no better.
-//
-// Every kernel over a layer list walks the chunk table from its workgroup number in steps of
-// the grid size.  Normally the grid has one workgroup per chunk and the loop runs once; a plan
-// with a workgroup limit (cdsgd_plan_set_max_workgroups) launches fewer workgroups, which then
-// take several chunks each and leave compute units free for other kernels.
+// Every kernel over a layer list walks the pieces of the chunk table from its workgroup number
+// in steps of the grid size.  Normally the grid has one workgroup per piece and the loop runs
+// once; a plan with a workgroup limit (cdsgd_plan_set_max_workgroups) launches fewer
+// workgroups, which then take several pieces each and leave compute units free for other
+// kernels.  How pieces are dealt to the 8 XCDs is piece_of_workgroup's business.
 
 // ---------------------------------------------------------------------------
 // kernels

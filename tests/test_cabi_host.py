@@ -37,6 +37,25 @@ def test_header_declares_the_named_entry_points():
         assert must in names
 
 
+def test_binding_constants_match_the_header():
+    from paper_2106_10796_amd import binding
+    src = "\n".join(open(h).read() for h in HEADERS)
+    defines = {k: int(v) for k, v in re.findall(r"#define\s+(CDSGD_[A-Z_]+)\s+(\d+)", src)}
+    assert defines["CDSGD_MAX_WORKERS"] == binding.MAX_WORKERS
+    assert defines["CDSGD_STATIC_MAX_TENSORS"] == binding.STATIC_MAX_TENSORS
+    assert defines["CDSGD_STATIC_MAX_CHUNKS"] == binding.STATIC_MAX_CHUNKS
+    assert defines["CDSGD_STATIC_CHUNK_ELEMS"] == binding.STATIC_CHUNK_ELEMS
+    enums = dict(re.findall(r"(CDSGD_[A-Z0-9_]+)\s*=\s*(\d+)", src))
+    for name, val in (("CDSGD_OK", binding.OK), ("CDSGD_ERR_NULL", binding.ERR_NULL), ("CDSGD_ERR_SIZE", binding.ERR_SIZE),
+                      ("CDSGD_ERR_PARAM", binding.ERR_PARAM), ("CDSGD_ERR_ALIGN", binding.ERR_ALIGN),
+                      ("CDSGD_ERR_WORKERS", binding.ERR_WORKERS), ("CDSGD_ERR_DEVICE", binding.ERR_DEVICE),
+                      ("CDSGD_ERR_ALIAS", binding.ERR_ALIAS), ("CDSGD_PEERS_PACKED", binding.PEERS_PACKED),
+                      ("CDSGD_PEERS_SPARSE", binding.PEERS_SPARSE), ("CDSGD_PASS_WARMUP", binding.PASS_WARMUP),
+                      ("CDSGD_PASS_COMPRESSED", binding.PASS_COMPRESSED), ("CDSGD_PASS_CORRECTION", binding.PASS_CORRECTION),
+                      ("CDSGD_GRAD_BF16", 1), ("CDSGD_GRAD_F16", 2)):
+        assert int(enums[name]) == val, name
+
+
 def test_library_exports_every_declared_symbol(L):
     for name in declared_functions():
         assert hasattr(L, name), name

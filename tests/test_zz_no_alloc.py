@@ -122,6 +122,45 @@ def test_static_step_matches_plan_step_on_calls_in_a_row(B):
     _run_pair(B, rng, [77], N=2, self_rank=1, t=0.5, steps=[1, 2], k=3, grad_dtype=torch.float16)
 
 
+def test_static_steps_replay_from_a_hip_graph(B):
+    """What the entry point is for: it enqueues kernels only (the tables travel in kernel arguments), so a
+    period of steps can be captured in a HIP graph and replayed.  Replays, with eager work in between, must
+    leave exactly what the same steps through a plan leave."""
+    rng = np.random.default_rng(909)
+    sizes, N, self_rank, k, t = [4097, 300, 12288, 5], 6, 4, 3, 0.5
+    copies, peers = _make_case(B, rng, sizes, N, self_rank, t, torch.float32)
+    plan = B.Plan(copies[0][1], peers, N, self_rank)
+    period = list(range(k))                   # one correction pass, k - 1 compressed passes
+
+    def run_static():
+        for s in period:
+            B.cdsgd_step_fused_static(copies[1][1], peers, N, self_rank, s, k, t, 0.4, 0.1)
+
+    def run_plan():
+        for s in period:
+            plan.step(s, k, t, 0.4, 0.1)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):             # warm-up on the capture stream (also looks the array's address up)
+        run_static()
+    torch.cuda.current_stream().wait_stream(side)
+    run_plan()
+    torch.cuda.synchronize()
+    _assert_same(copies, "before the capture")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run_static()
+    for rep in range(4):
+        graph.replay()
+        run_plan()
+        torch.cuda.synchronize()
+        junk = torch.randn(1 << 18, device="cuda").sum().item()     # eager work between the replays
+        assert junk == junk
+        _assert_same(copies, "after replay %d" % rep)
+    plan.destroy()
+
+
 def test_static_step_limits_and_errors(B):
     """Sizes beyond the static array's limits and missing inputs are refused before anything runs."""
     n = 64
