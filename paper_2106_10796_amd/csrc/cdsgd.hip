@@ -1263,7 +1263,9 @@ const char *cdsgd_status_string(int status)
     switch (status) {
     case CDSGD_OK: return "ok";
     case CDSGD_ERR_NULL: return "a required pointer is NULL";
-    case CDSGD_ERR_SIZE: return "bad size (zero elements, no tensors, or too large for one launch)";
+    case CDSGD_ERR_SIZE:
+        return "bad size (zero elements, no tensors, too large for one launch, or beyond the limits of "
+               "cdsgd_step_fused_static's tables)";
     case CDSGD_ERR_PARAM: return "bad parameter (threshold, k, step or learning rate)";
     case CDSGD_ERR_ALIGN: return "pointer not aligned (fp32 buffers 16 bytes, packed buffers 4 bytes)";
     case CDSGD_ERR_WORKERS: return "bad worker count or worker index";
