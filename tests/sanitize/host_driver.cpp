@@ -40,6 +40,37 @@ int main()
     bad += cdsgd_trainer_create(reinterpret_cast<cdsgd_plan *>(A), 2, 4, 0.5f, 0.1f, 0.1f, &tr) != CDSGD_OK;
     bad += cdsgd_trainer_iteration(tr) != 0;
     bad += cdsgd_trainer_destroy(tr) != CDSGD_OK;
+    // the entry point that allocates nothing: every check that comes before its first HIP call
+    {
+        float *B0 = reinterpret_cast<float *>(0x100000), *B1 = reinterpret_cast<float *>(0x200000);
+        float *B2 = reinterpret_cast<float *>(0x300000), *B3 = reinterpret_cast<float *>(0x400000);
+        uint32_t *B4 = reinterpret_cast<uint32_t *>(0x500000), *B5 = reinterpret_cast<uint32_t *>(0x600000);
+        cdsgd_tensor u = {B0, B1, B2, B3, B4, nullptr, 1000};
+        const uint32_t *urow[1] = {B5};
+        const uint32_t *const *urows[2] = {nullptr, urow};
+        bad += cdsgd_step_fused_static(nullptr, 1, urows, 2, 0, 0, 1, 4, 0.5f, 0.1f, 0.1f, nullptr) != CDSGD_ERR_NULL;
+        bad += cdsgd_step_fused_static(&u, 1, urows, 2, 0, 9, 1, 4, 0.5f, 0.1f, 0.1f, nullptr) != CDSGD_ERR_PARAM;
+        bad += cdsgd_step_fused_static(&u, 1, urows, 2, 0, 0, 1, 0, 0.5f, 0.1f, 0.1f, nullptr) != CDSGD_ERR_PARAM;
+        bad += cdsgd_step_fused_static(&u, 1, urows, 2, 0, 0, 0, 4, 0.5f, 0.1f, 0.1f, nullptr) != CDSGD_ERR_NULL;  // no agg_full
+        bad += cdsgd_step_fused_static(&u, 1, urows, 2, 3, 0, 1, 4, 0.5f, 0.1f, 0.1f, nullptr) != CDSGD_ERR_WORKERS;
+        std::vector<cdsgd_tensor> many(CDSGD_STATIC_MAX_TENSORS + 1, u);
+        std::vector<const uint32_t *> manyrow(many.size(), B5);
+        const uint32_t *const *manyrows[2] = {nullptr, manyrow.data()};
+        bad += cdsgd_step_fused_static(many.data(), (int)many.size(), manyrows, 2, 0, 0, 1, 4, 0.5f, 0.1f, 0.1f, nullptr) !=
+               CDSGD_ERR_SIZE;
+        u.w_local = B0 + 4;  // overlaps w_global
+        bad += cdsgd_step_fused_static(&u, 1, urows, 2, 0, 0, 1, 4, 0.5f, 0.1f, 0.1f, nullptr) != CDSGD_ERR_ALIAS;
+    }
+    // sparse form: sizes and argument checks
+    bad += cdsgd_sparse_segments(4097) != 2 || cdsgd_sparse_words(4097) != 528;
+    bad += cdsgd_sparse_encode(nullptr, 16, P, nullptr, nullptr) != CDSGD_ERR_NULL;
+    bad += cdsgd_sparse_encode(P, 0, P + 4096, nullptr, nullptr) != CDSGD_ERR_SIZE;
+    bad += cdsgd_sparse_encode(P, 64, P, nullptr, nullptr) != CDSGD_ERR_ALIAS;
+    bad += cdsgd_decode_sum_sparse(two, 2, A, 16, 0.5f, nullptr) != CDSGD_ERR_NULL;
+    bad += cdsgd_plan_set_peer_format(nullptr, CDSGD_PEERS_SPARSE) != CDSGD_ERR_NULL;
+    bad += cdsgd_plan_set_max_workgroups(nullptr, 1) != CDSGD_ERR_NULL;
+    bad += cdsgd_plan_set_thresholds(nullptr, nullptr) != CDSGD_ERR_NULL;
+    bad += cdsgd_build_id() == nullptr;
     cdsgd_cost_params p = {1.0, 5.0, 1.0, 0.5, 4};
     cdsgd_cost c;
     double sum = 0;

@@ -19,6 +19,8 @@ int oracle_trainer_step(float *w_global, float *w_local, float *const *residual,
                         int num_workers, int self, long iter, long warmup_n, int k, float t, float lr_local,
                         float lr_global);
 void oracle_cost_model(double tau, double phi, double psi, double delta, int k, long i, double *out);
+void oracle_sparse_encode(const uint32_t *word, size_t n, uint32_t *sparse, uint32_t *seg_words);
+void oracle_sparse_decode(const uint32_t *sparse, size_t n, uint32_t *word);
 
 static uint32_t rng_state = 12345u;
 static float rnd(void)
@@ -68,6 +70,26 @@ int main(void)
         free(L);
         free(agg);
         free(code);
+    }
+    /* sparse form on exactly-sized buffers: sizes around the 256-word segment edge, sparse and dense words */
+    const size_t ssizes[] = {1, 16, 17, 4095, 4096, 4097, 8192, 8200, 3 * 4096 + 5};
+    for (size_t si = 0; si < sizeof(ssizes) / sizeof(ssizes[0]); ++si) {
+        size_t n = ssizes[si], nw = (n + 15) / 16, nseg = (nw + 255) / 256;
+        uint32_t *word = malloc(nw * sizeof(uint32_t)), *back = malloc(nw * sizeof(uint32_t));
+        uint32_t *sparse = malloc(nseg * 264 * sizeof(uint32_t)), *seg = malloc(nseg * sizeof(uint32_t));
+        for (int dense = 0; dense < 2; ++dense) {
+            for (size_t w = 0; w < nw; ++w) word[w] = (dense || rnd() > 0.8f) ? (rng_state | 1u) : 0u;
+            for (size_t x = 0; x < nseg * 264; ++x) sparse[x] = 0xA5A5A5A5u;
+            oracle_sparse_encode(word, n, sparse, seg);
+            oracle_sparse_encode(word, n, sparse, NULL);
+            oracle_sparse_decode(sparse, n, back);
+            for (size_t w = 0; w < nw; ++w) check += (back[w] == word[w]) ? 0.0 : 1e9;
+            for (size_t x = 0; x < nseg; ++x) check += seg[x];
+        }
+        free(word);
+        free(back);
+        free(sparse);
+        free(seg);
     }
     double out[7];
     for (long i = 0; i < 12; ++i) {
