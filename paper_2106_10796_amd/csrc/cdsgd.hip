@@ -1068,7 +1068,9 @@ inline Extent extent_of_units(size_t n, unsigned unit_quads)
     return e;
 }
 
-constexpr unsigned long long kMaxGrid = 0x7FFFFFFFull;
+// Most chunks (or segments) a tensor or a layer list may have: a launch of one workgroup of up to
+// 1024 lanes per chunk stays below 2^32 threads (1.7e10 elements).
+constexpr unsigned long long kMaxGrid = 0xFFFFFFFFull / 1024;
 constexpr unsigned kQuantLanes = 64;  // lanes = quads of a piece of k_quantize_pack
 
 // A threshold 2^e (moderate e): every multiple m*t, |m| <= 2*CDSGD_MAX_WORKERS, is exact.
@@ -1112,13 +1114,15 @@ struct PlanTables {
     unsigned max_workgroups = 0;       // > 0: launch at most this many workgroups (they take several chunks each)
     bool peers_sparse = false;         // the peers' streams are in the sparse form (cdsgd_plan_set_peer_format)
 
-    // Workgroups to launch for `units` units of work (chunks, or pieces of chunks).
-    unsigned grid_size(unsigned long long units) const
+    // Workgroups of `lanes` lanes to launch for `units` units of work (pieces of chunks): one per unit,
+    // unless the plan has a limit or the launch would pass 2^32 - 1 threads (the kernels walk the units
+    // with the grid's stride, so fewer workgroups than units is always correct).
+    unsigned grid_size(unsigned long long units, unsigned lanes) const
     {
-        const unsigned long long cap = max_workgroups != 0 ? max_workgroups : 0x7FFFFFFFull;
+        unsigned long long cap = 0xFFFFFFFFull / lanes;
+        if (max_workgroups != 0 && max_workgroups < cap) cap = max_workgroups;
         return (unsigned)(units < cap ? units : cap);
     }
-    unsigned grid_size() const { return grid_size(num_chunks); }
 };
 
 struct cdsgd_plan : PlanTables {
@@ -1216,7 +1220,7 @@ int launch_full_pass(const PlanTables *plan, int local_mode, float lr_local, flo
     const float scale = lr_global / (float)plan->num_workers;
     hipStream_t s = (hipStream_t)hip_stream;
     const unsigned long long num_pieces = (unsigned long long)plan->num_chunks * kPiecesPerChunk;
-    const dim3 grid(plan->grid_size(num_pieces)), block(kFullBlock);
+    const dim3 grid(plan->grid_size(num_pieces, kFullBlock)), block(kFullBlock);
     const int np = plan->num_workers - 1;
 #define CDSGD_LAUNCH_FULL_T(SUM, LOCAL, GT)                                                                    \
     hipLaunchKernelGGL((k_fused_full<SUM, LOCAL, GT>), grid, block, 0, s, plan->tensors, plan->chunks,           \
@@ -1279,7 +1283,7 @@ int cdsgd_quantize_pack(const float *grad, float *residual, uint32_t *packed, si
                         void *hip_stream)
 {
     if (!grad || !residual || !packed) return CDSGD_ERR_NULL;
-    if (n == 0 || units_of(n, kQuantLanes) > kMaxGrid) return CDSGD_ERR_SIZE;
+    if (n == 0 || units_of(n, kQuantLanes) > 0xFFFFFFFFull / kQuantLanes) return CDSGD_ERR_SIZE;
     if (!good_threshold(threshold)) return CDSGD_ERR_PARAM;
     if (!aligned(grad, 16) || !aligned(residual, 16) || !aligned(packed, 4)) return CDSGD_ERR_ALIGN;
     if (overlap(grad, residual, n * sizeof(float)) ||
@@ -1456,7 +1460,7 @@ int launch_formal_pass(const PlanTables *plan, long step, int k, float threshold
     const int num_peers = plan->num_workers - 1;
     const unsigned waves = num_peers <= kFewPeers ? 1u : kPieceWavesMany;
     const unsigned long long num_pieces = (unsigned long long)plan->num_chunks * (kChunkQuads / (64u * waves));
-    const dim3 grid(plan->grid_size(num_pieces)), block(64u * waves);
+    const dim3 grid(plan->grid_size(num_pieces, 64u * waves)), block(64u * waves);
 #define CDSGD_LAUNCH_COMPRESSED_S(W, POW2, LOCAL, GT, SPARSE)                                                  \
     hipLaunchKernelGGL((k_fused_compressed<W, POW2, LOCAL, GT, SPARSE>), grid, block, 0, s, plan->tensors,      \
                        plan->chunks, num_pieces, plan->peers, num_peers, plan->self, threshold, lr_local, scale)
@@ -1505,7 +1509,7 @@ int cdsgd_step_local(cdsgd_plan *plan, float lr_local, void *hip_stream)
     if (!plan) return CDSGD_ERR_NULL;
     if (!std::isfinite(lr_local)) return CDSGD_ERR_PARAM;
     const unsigned long long num_pieces = (unsigned long long)plan->num_chunks * kPiecesPerChunk;
-    const dim3 grid(plan->grid_size(num_pieces)), block(kFullBlock);
+    const dim3 grid(plan->grid_size(num_pieces, kFullBlock)), block(kFullBlock);
     hipStream_t s = (hipStream_t)hip_stream;
 #define CDSGD_LAUNCH_LOCAL(GT)                                                                                 \
     hipLaunchKernelGGL((k_fused_full<false, kLocalOnly, GT>), grid, block, 0, s, plan->tensors, plan->chunks,    \
