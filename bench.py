@@ -148,18 +148,33 @@ def time_workload(name, steps, warmup, want_correction=True, want_unfused=False,
 
 def stream_ceilings(wl, min_seconds=0.3):
     """What plain streaming kernels reach on this GPU, on the same arenas and in the same run, for
-    comparison with the library's kernels: a fill (writes only), a sum (reads only), a copy
-    (1 read, 1 write) and an add (2 reads, 1 write).  These are torch's own elementwise kernels: harness, not product."""
+    comparison with the library's kernels.  Two families: the library's own bare streaming kernel
+    (cdsgd_probe_streams: the loads, stores and launch shape of its passes on 32-bit gradients, no
+    arithmetic) for several mixes of read and write streams, and torch's elementwise kernels (fill,
+    sum, copy, add).  Harness, not product: nothing here is on the path that is being measured."""
     import torch
+    from paper_2106_10796_amd import binding
     stream = torch.cuda.current_stream()
     n = wl.w_global.numel()
-    a, b, c = wl.w_global, wl.residual, wl.w_local
+    a, b, g = wl.w_global, wl.residual, wl.grad                      # read only (the CPU baseline still needs them)
+    c, d = wl.w_local, wl.agg_full                                   # free to overwrite now
+    e = torch.empty_like(c)
+    sink = torch.zeros(n // 256, dtype=torch.float32, device=c.device)
+    fp32_grad = g.dtype == torch.float32
     ops = {"fill_write_only": (lambda: c.fill_(1.0), 4.0 * n),
            "sum_read_only": (lambda: torch.sum(a), 4.0 * n),
            "copy_1r_1w": (lambda: c.copy_(a), 8.0 * n),
            "add_2r_1w": (lambda: torch.add(a, b, out=c), 12.0 * n)}
-    out = {"elements": n, "note": "torch elementwise kernels on the workload's own fp32 arenas, >= %.1f s each, "
-                                  "after the headline (warm GPU)" % min_seconds}
+    probe = {"probe_1r_0w": ([a], []), "probe_0r_1w": ([], [c]), "probe_1r_1w": ([a], [c]), "probe_2r_1w": ([a, b], [c])}
+    if fp32_grad:
+        probe.update({"probe_3r_0w": ([a, b, g], []), "probe_3r_2w": ([a, b, g], [c, d]),
+                      "probe_3r_3w": ([a, b, g], [c, d, e])})
+    for name, (rd, wr) in probe.items():
+        ops[name] = ((lambda rd=rd, wr=wr: binding.cdsgd_probe_streams(rd, wr, sink)), 4.0 * n * (len(rd) + len(wr)))
+    out = {"elements": n,
+           "note": "GB/s of bare streaming on the workload's own fp32 arenas, >= %.1f s each, after the headline (warm "
+                   "GPU): probe_<R>r_<W>w = the library's streaming probe with R read and W write streams "
+                   "(cdsgd_probe_streams), the others torch's elementwise kernels" % min_seconds}
     for name, (fn, nbytes) in ops.items():
         for _ in range(3):
             fn()
@@ -175,6 +190,8 @@ def stream_ceilings(wl, min_seconds=0.3):
             total_ms += e0.elapsed_time(e1)
             calls += 20
         out[name + "_gbs"] = nbytes / (total_ms / calls * 1e-3) / 1e9
+    del e, sink
+    torch.cuda.empty_cache()
     return out
 
 

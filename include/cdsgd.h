@@ -314,6 +314,20 @@ long cdsgd_trainer_iteration(const cdsgd_trainer *trainer);
 int cdsgd_trainer_destroy(cdsgd_trainer *trainer);
 
 /*
+ * Measurement aid, not part of the method: a bare streaming kernel that reads num_reads (0..3) fp32
+ * buffers of n elements and writes num_writes (0..3) others (the sum of what it read, plus the
+ * stream's index), with the loads, stores and launch shape of the passes on 32-bit gradients and no
+ * other arithmetic.  A benchmark uses it to state what the memory system gives a kernel with a given
+ * mix of read and write streams, next to what the fused kernels reach with theirs.
+ *   reads / writes  HOST arrays of DEVICE pointers to fp32[n], 16-byte aligned, pairwise distinct
+ *   n               a multiple of 256
+ *   sink            device buffer of n / 256 floats, needed (and practically never written) when
+ *                   num_writes == 0; may be NULL otherwise
+ */
+int cdsgd_probe_streams(const float *const *reads, int num_reads, float *const *writes, int num_writes,
+                        size_t n, float *sink, void *hip_stream);
+
+/*
  * cdsgd_step_fused for callers that cannot allocate device memory: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same pass, same results
  * and same argument checks as cdsgd_plan_create_typed followed by cdsgd_step_fused on that

@@ -94,6 +94,8 @@ def lib():
         L.cdsgd_decode_sum_sparse.argtypes = [ctypes.POINTER(vp), i, vp, sz, f, vp]
         L.cdsgd_plan_set_peer_format.restype = i
         L.cdsgd_plan_set_peer_format.argtypes = [vp, i]
+        L.cdsgd_probe_streams.restype = i
+        L.cdsgd_probe_streams.argtypes = [ctypes.POINTER(vp), i, ctypes.POINTER(vp), i, sz, vp, vp]
         L.cdsgd_plan_set_max_workgroups.restype = i
         L.cdsgd_plan_set_max_workgroups.argtypes = [vp, i]
         L.cdsgd_step_local.restype = i
@@ -204,6 +206,16 @@ def cdsgd_decode_sum_sparse(sparse_list, agg, threshold):
         arr[j] = _dev(p, PACKED_DTYPE, sparse_words(n), "sparse[%d]" % j)
     st = lib().cdsgd_decode_sum_sparse(arr, N, _dev(agg, torch.float32, None, "agg"), n, float(threshold), _stream())
     _check(st, "cdsgd_decode_sum_sparse")
+
+
+def cdsgd_probe_streams(reads, writes, sink=None):
+    """Bare streaming of len(reads) read and len(writes) write streams (cdsgd_probe_streams)."""
+    n = (reads + writes)[0].numel()
+    ra = (ctypes.c_void_p * max(len(reads), 1))(*[_dev(t, torch.float32, n, "reads").value for t in reads])
+    wa = (ctypes.c_void_p * max(len(writes), 1))(*[_dev(t, torch.float32, n, "writes").value for t in writes])
+    st = lib().cdsgd_probe_streams(ra, len(reads), wa, len(writes), n,
+                                   _dev(sink, torch.float32, None, "sink"), _stream())
+    _check(st, "cdsgd_probe_streams")
 
 
 def cdsgd_update(w_global, w_local, grad_local, agg, lr_local, lr_global, num_workers):

@@ -644,6 +644,36 @@ __global__ __launch_bounds__(L) void k_quantize_pack(const float *__restrict__ g
     }
 }
 
+// ---------------------------------------------------------------------------
+// Measurement aid: bare streaming with a given mix of read and write streams
+// ---------------------------------------------------------------------------
+// One wave per 64-quad piece, non-temporal 128-bit loads and stores, no arithmetic beyond adding
+// what was read: what the memory system gives a kernel that moves R + W streams the way the fused
+// kernels move theirs.  With W == 0 the sum goes to `sink` only if it has a value it cannot have.
+struct ProbeStreams {
+    const float *r[4];
+    float *w[4];
+};
+
+template <int R, int W>
+__global__ __launch_bounds__(64) void k_probe_streams(ProbeStreams p, float *sink)
+{
+    const size_t quad0 = (size_t)blockIdx.x * 64u;
+    const unsigned lane = threadIdx.x;
+    f4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    f4 v[R > 0 ? R : 1];
+#pragma unroll
+    for (int i = 0; i < R; ++i) v[i] = ld4(p.r[i] + 4 * quad0, lane);
+#pragma unroll
+    for (int i = 0; i < R; ++i) acc = acc + v[i];
+#pragma unroll
+    for (int i = 0; i < W; ++i) st4(p.w[i] + 4 * quad0, lane, acc + (float)i);
+    if (W == 0) {
+        const float s = acc.x + acc.y + acc.z + acc.w;
+        if (s == -1.2345678e30f) sink[blockIdx.x] = s;
+    }
+}
+
 // Piece-granular kernels: which piece workgroup b takes.  Workgroup b runs on XCD b % 8.  Within
 // a block of 8 chunks' worth of workgroups, XCD k takes every piece of chunk k, so that the two
 // halves of a 128-byte line of a peer's codes, and the pieces' reads of the chunk's table
@@ -1634,6 +1664,53 @@ int cdsgd_plan_set_peer_format(cdsgd_plan *plan, int format)
     if (format != CDSGD_PEERS_PACKED && format != CDSGD_PEERS_SPARSE) return CDSGD_ERR_PARAM;
     plan->peers_sparse = format == CDSGD_PEERS_SPARSE;
     return CDSGD_OK;
+}
+
+int cdsgd_probe_streams(const float *const *reads, int num_reads, float *const *writes, int num_writes, size_t n,
+                        float *sink, void *hip_stream)
+{
+    if (num_reads < 0 || num_reads > 3 || num_writes < 0 || num_writes > 3 || num_reads + num_writes == 0)
+        return CDSGD_ERR_PARAM;
+    if ((num_reads > 0 && !reads) || (num_writes > 0 && !writes) || (num_writes == 0 && !sink)) return CDSGD_ERR_NULL;
+    if (n == 0 || n % 256 != 0 || n / 256 > 0xFFFFFFFFull / 64) return CDSGD_ERR_SIZE;
+    ProbeStreams p;
+    std::memset(&p, 0, sizeof(p));
+    for (int i = 0; i < num_reads; ++i) {
+        if (!reads[i]) return CDSGD_ERR_NULL;
+        if (!aligned(reads[i], 16)) return CDSGD_ERR_ALIGN;
+        p.r[i] = reads[i];
+    }
+    for (int i = 0; i < num_writes; ++i) {
+        if (!writes[i]) return CDSGD_ERR_NULL;
+        if (!aligned(writes[i], 16)) return CDSGD_ERR_ALIGN;
+        for (int j = 0; j < num_reads; ++j)
+            if (overlap(writes[i], reads[j], n * sizeof(float))) return CDSGD_ERR_ALIAS;
+        for (int j = 0; j < i; ++j)
+            if (overlap(writes[i], writes[j], n * sizeof(float))) return CDSGD_ERR_ALIAS;
+        p.w[i] = writes[i];
+    }
+    const dim3 grid((unsigned)(n / 256)), block(64);
+    hipStream_t s = (hipStream_t)hip_stream;
+#define CDSGD_PROBE(R, W) hipLaunchKernelGGL((k_probe_streams<R, W>), grid, block, 0, s, p, sink)
+    switch (num_reads * 4 + num_writes) {
+    case 0 * 4 + 1: CDSGD_PROBE(0, 1); break;
+    case 0 * 4 + 2: CDSGD_PROBE(0, 2); break;
+    case 0 * 4 + 3: CDSGD_PROBE(0, 3); break;
+    case 1 * 4 + 0: CDSGD_PROBE(1, 0); break;
+    case 1 * 4 + 1: CDSGD_PROBE(1, 1); break;
+    case 1 * 4 + 2: CDSGD_PROBE(1, 2); break;
+    case 1 * 4 + 3: CDSGD_PROBE(1, 3); break;
+    case 2 * 4 + 0: CDSGD_PROBE(2, 0); break;
+    case 2 * 4 + 1: CDSGD_PROBE(2, 1); break;
+    case 2 * 4 + 2: CDSGD_PROBE(2, 2); break;
+    case 2 * 4 + 3: CDSGD_PROBE(2, 3); break;
+    case 3 * 4 + 0: CDSGD_PROBE(3, 0); break;
+    case 3 * 4 + 1: CDSGD_PROBE(3, 1); break;
+    case 3 * 4 + 2: CDSGD_PROBE(3, 2); break;
+    default: CDSGD_PROBE(3, 3); break;
+    }
+#undef CDSGD_PROBE
+    return launch_status();
 }
 
 int cdsgd_plan_set_max_workgroups(cdsgd_plan *plan, int max_workgroups)

@@ -69,6 +69,14 @@ int main()
     bad += cdsgd_decode_sum_sparse(two, 2, A, 16, 0.5f, nullptr) != CDSGD_ERR_NULL;
     bad += cdsgd_plan_set_peer_format(nullptr, CDSGD_PEERS_SPARSE) != CDSGD_ERR_NULL;
     bad += cdsgd_plan_set_max_workgroups(nullptr, 1) != CDSGD_ERR_NULL;
+    {
+        const float *rd[3] = {A, A + 4096, A + 8192};
+        float *wr[3] = {A + 12288, A + 16384, A + 12288 + 4};
+        bad += cdsgd_probe_streams(rd, 4, wr, 1, 1024, A, nullptr) != CDSGD_ERR_PARAM;
+        bad += cdsgd_probe_streams(rd, 3, wr, 0, 1024, nullptr, nullptr) != CDSGD_ERR_NULL;
+        bad += cdsgd_probe_streams(rd, 3, wr, 2, 1000, nullptr, nullptr) != CDSGD_ERR_SIZE;
+        bad += cdsgd_probe_streams(rd, 3, wr, 3, 1024, nullptr, nullptr) != CDSGD_ERR_ALIAS;
+    }
     bad += cdsgd_plan_set_thresholds(nullptr, nullptr) != CDSGD_ERR_NULL;
     bad += cdsgd_build_id() == nullptr;
     cdsgd_cost_params p = {1.0, 5.0, 1.0, 0.5, 4};

@@ -33,7 +33,7 @@ def test_header_declares_the_named_entry_points():
                  "cdsgd_step_local", "cdsgd_step_global", "cdsgd_cost_iteration", "cdsgd_cost_period_mean",
                  "cdsgd_plan_create_typed", "cdsgd_plan_set_thresholds", "cdsgd_plan_set_max_workgroups",
                  "cdsgd_step_fused_static", "cdsgd_build_id", "cdsgd_sparse_encode", "cdsgd_decode_sum_sparse",
-                 "cdsgd_sparse_words", "cdsgd_sparse_segments", "cdsgd_plan_set_peer_format"):
+                 "cdsgd_sparse_words", "cdsgd_sparse_segments", "cdsgd_plan_set_peer_format", "cdsgd_probe_streams"):
         assert must in names
 
 
@@ -105,6 +105,24 @@ def test_sparse_sizes_and_argument_errors(L):
     assert d(two, 2, A + 0x20004, 16, 0.5, None) == ERR_ALIGN
     assert d(two, 2, A + 64, 16, 0.5, None) == ERR_ALIAS
     assert L.cdsgd_plan_set_peer_format(None, 0) == ERR_NULL
+
+
+def test_probe_streams_argument_errors(L):
+    from paper_2106_10796_amd.binding import ERR_ALIAS, ERR_ALIGN, ERR_NULL, ERR_PARAM, ERR_SIZE
+    f = L.cdsgd_probe_streams
+    r = (ctypes.c_void_p * 3)(A, A + 0x100000, A + 0x200000)
+    w = (ctypes.c_void_p * 3)(A + 0x300000, A + 0x400000, A + 0x500000)
+    S = A + 0x600000
+    assert f(r, 4, w, 1, 1024, S, None) == ERR_PARAM
+    assert f(r, 0, w, 0, 1024, S, None) == ERR_PARAM
+    assert f(None, 1, w, 1, 1024, S, None) == ERR_NULL
+    assert f(r, 2, w, 0, 1024, None, None) == ERR_NULL            # read-only needs the sink
+    assert f(r, 1, w, 1, 1000, S, None) == ERR_SIZE              # not a multiple of 256
+    assert f(r, 1, w, 1, 0, S, None) == ERR_SIZE
+    odd = (ctypes.c_void_p * 1)(A + 4)
+    assert f(odd, 1, w, 1, 1024, S, None) == ERR_ALIGN
+    assert f(r, 1, r, 1, 1024, S, None) == ERR_ALIAS             # writing what is read
+    assert f(r, 1, (ctypes.c_void_p * 2)(A + 0x300000, A + 0x300010), 2, 1024, S, None) == ERR_ALIAS
 
 
 def test_status_strings(L):

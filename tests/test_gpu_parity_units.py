@@ -136,6 +136,29 @@ def test_update(B, oracle, n, mode):
     assert guards_intact(wfull, n, 5.0) and guards_intact(lfull, n, 6.0)
 
 
+def test_probe_streams_moves_what_it_says(B):
+    """The measurement aid: every write stream receives the sum of the read streams plus its index,
+    nothing outside the buffers is touched, a read-only run writes nothing."""
+    rng = np.random.default_rng(3500)
+    n = 256 * 37
+    reads = [torch.from_numpy(rng.normal(0, 1, n).astype(np.float32)).cuda() for _ in range(3)]
+    for R in range(0, 4):
+        for W in range(0, 4):
+            if R + W == 0:
+                continue
+            fulls = [guarded(n, torch.float32, 4.0) for _ in range(W)]
+            sink = torch.full((n // 256,), 7.0, device="cuda")
+            B.cdsgd_probe_streams(reads[:R], [v for _, v in fulls], sink)
+            torch.cuda.synchronize()
+            want = np.zeros(n, np.float32)
+            for i in range(R):
+                want = want + reads[i].cpu().numpy()              # same order of adds as the kernel
+            for i, (full, v) in enumerate(fulls):
+                assert_bits_equal(v.cpu().numpy(), (want + np.float32(i)).astype(np.float32), "probe R=%d W=%d stream %d" % (R, W, i))
+                assert guards_intact(full, n, 4.0)
+            assert bool((sink == 7.0).all())
+
+
 def _run_layer_list(B, oracle, sizes, N, self_rank, k, t, steps, seed, lr_l=0.4, lr_g=0.1):
     """Fused step vs oracle vs the three-call composition on an arbitrary layer list."""
     rng = np.random.default_rng(seed)
