@@ -252,10 +252,23 @@ def time_correction_sum(name, steps, warmup, min_seconds=0.5):
                           min_blocks=5)
     ms = blocks["median_ms_per_step"]
     bpe = 12.0 + 4.0 * cfg.num_workers
+    out = {"ms_per_step": ms, "blocks": blocks, "bytes_per_element": bpe,
+           "gbs": cfg.elements * bpe / (ms * 1e-3) / 1e9,
+           "frac_hbm_peak": cfg.elements * bpe / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    # the same mix of streams moved by the bare streaming probe: N + 1 reads (W, N gradients), 2 writes
+    if wl.grad.dtype == torch.float32 and cfg.num_workers + 1 <= 17:
+        from paper_2106_10796_amd import binding
+        reads = [wl.w_global, wl.grad] + [g for g in wl.peer_grad if g is not None]
+        writes = [wl.w_local, wl.agg_full]
+        probe = lambda: [binding.cdsgd_probe_streams(reads, writes) for _ in range(steps)]
+        probe()
+        pb = timed_blocks(probe, steps, stream, min_seconds=min_seconds, min_blocks=5)
+        nbytes = 4.0 * wl.w_global.numel() * (len(reads) + len(writes))
+        out["bare_streaming_same_mix"] = {"reads": len(reads), "writes": len(writes), "ms": pb["median_ms_per_step"],
+                                          "gbs": nbytes / (pb["median_ms_per_step"] * 1e-3) / 1e9,
+                                          "note": "cdsgd_probe_streams on the same arenas (pad included)"}
     wl.destroy()
-    return {"ms_per_step": ms, "blocks": blocks, "bytes_per_element": bpe,
-            "gbs": cfg.elements * bpe / (ms * 1e-3) / 1e9,
-            "frac_hbm_peak": cfg.elements * bpe / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    return out
 
 
 def overlap_demo(name, iters=16):

@@ -314,11 +314,15 @@ long cdsgd_trainer_iteration(const cdsgd_trainer *trainer);
 int cdsgd_trainer_destroy(cdsgd_trainer *trainer);
 
 /*
- * Measurement aid, not part of the method: a bare streaming kernel that reads num_reads (0..3) fp32
- * buffers of n elements and writes num_writes (0..3) others (the sum of what it read, plus the
- * stream's index), with the loads, stores and launch shape of the passes on 32-bit gradients and no
- * other arithmetic.  A benchmark uses it to state what the memory system gives a kernel with a given
- * mix of read and write streams, next to what the fused kernels reach with theirs.
+ * Measurement aid, not part of the method: a bare streaming kernel that reads num_reads (0..17) fp32
+ * buffers of n elements and writes num_writes (0..3) others (the sum of what it read, added in the
+ * order given, plus the stream's index), with the loads, stores and launch shape of the passes on
+ * 32-bit gradients and no other arithmetic.  Up to 3 read streams are loaded together; beyond that
+ * they are read one after the other, the way a correction pass reads the workers' gradients.  A
+ * benchmark uses it to state what the memory system gives a kernel with a given mix of read and
+ * write streams, next to what the fused kernels reach with theirs.
+ *   CDSGD_ERR_PARAM for counts outside those ranges or both zero, CDSGD_ERR_SIZE for n not a positive
+ *   multiple of 256, CDSGD_ERR_ALIAS when a written buffer overlaps another buffer.
  *   reads / writes  HOST arrays of DEVICE pointers to fp32[n], 16-byte aligned, pairwise distinct
  *   n               a multiple of 256
  *   sink            device buffer of n / 256 floats, needed (and practically never written) when

@@ -650,22 +650,30 @@ __global__ __launch_bounds__(L) void k_quantize_pack(const float *__restrict__ g
 // One wave per 64-quad piece, non-temporal 128-bit loads and stores, no arithmetic beyond adding
 // what was read: what the memory system gives a kernel that moves R + W streams the way the fused
 // kernels move theirs.  With W == 0 the sum goes to `sink` only if it has a value it cannot have.
+constexpr int kProbeMaxReads = 17, kProbeMaxWrites = 3;
 struct ProbeStreams {
-    const float *r[4];
-    float *w[4];
+    const float *r[kProbeMaxReads];
+    float *w[kProbeMaxWrites];
+    int num_reads;
 };
 
+// R >= 0: that many read streams, all loads in flight at once.  R < 0: p.num_reads streams, one
+// load in flight per lane (the order the correction pass reads the workers' gradients in).
 template <int R, int W>
 __global__ __launch_bounds__(64) void k_probe_streams(ProbeStreams p, float *sink)
 {
     const size_t quad0 = (size_t)blockIdx.x * 64u;
     const unsigned lane = threadIdx.x;
     f4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-    f4 v[R > 0 ? R : 1];
+    if (R >= 0) {
+        f4 v[R > 0 ? R : 1];
 #pragma unroll
-    for (int i = 0; i < R; ++i) v[i] = ld4(p.r[i] + 4 * quad0, lane);
+        for (int i = 0; i < R; ++i) v[i] = ld4(p.r[i] + 4 * quad0, lane);
 #pragma unroll
-    for (int i = 0; i < R; ++i) acc = acc + v[i];
+        for (int i = 0; i < R; ++i) acc = acc + v[i];
+    } else {
+        for (int i = 0; i < p.num_reads; ++i) acc = acc + ld4(p.r[i] + 4 * quad0, lane);
+    }
 #pragma unroll
     for (int i = 0; i < W; ++i) st4(p.w[i] + 4 * quad0, lane, acc + (float)i);
     if (W == 0) {
@@ -1669,12 +1677,14 @@ int cdsgd_plan_set_peer_format(cdsgd_plan *plan, int format)
 int cdsgd_probe_streams(const float *const *reads, int num_reads, float *const *writes, int num_writes, size_t n,
                         float *sink, void *hip_stream)
 {
-    if (num_reads < 0 || num_reads > 3 || num_writes < 0 || num_writes > 3 || num_reads + num_writes == 0)
+    if (num_reads < 0 || num_reads > kProbeMaxReads || num_writes < 0 || num_writes > kProbeMaxWrites ||
+        num_reads + num_writes == 0)
         return CDSGD_ERR_PARAM;
     if ((num_reads > 0 && !reads) || (num_writes > 0 && !writes) || (num_writes == 0 && !sink)) return CDSGD_ERR_NULL;
     if (n == 0 || n % 256 != 0 || n / 256 > 0xFFFFFFFFull / 64) return CDSGD_ERR_SIZE;
     ProbeStreams p;
     std::memset(&p, 0, sizeof(p));
+    p.num_reads = num_reads;
     for (int i = 0; i < num_reads; ++i) {
         if (!reads[i]) return CDSGD_ERR_NULL;
         if (!aligned(reads[i], 16)) return CDSGD_ERR_ALIGN;
@@ -1692,7 +1702,11 @@ int cdsgd_probe_streams(const float *const *reads, int num_reads, float *const *
     const dim3 grid((unsigned)(n / 256)), block(64);
     hipStream_t s = (hipStream_t)hip_stream;
 #define CDSGD_PROBE(R, W) hipLaunchKernelGGL((k_probe_streams<R, W>), grid, block, 0, s, p, sink)
-    switch (num_reads * 4 + num_writes) {
+    switch ((num_reads > 3 ? 4 : num_reads) * 4 + num_writes) {
+    case 4 * 4 + 0: CDSGD_PROBE(-1, 0); break;
+    case 4 * 4 + 1: CDSGD_PROBE(-1, 1); break;
+    case 4 * 4 + 2: CDSGD_PROBE(-1, 2); break;
+    case 4 * 4 + 3: CDSGD_PROBE(-1, 3); break;
     case 0 * 4 + 1: CDSGD_PROBE(0, 1); break;
     case 0 * 4 + 2: CDSGD_PROBE(0, 2); break;
     case 0 * 4 + 3: CDSGD_PROBE(0, 3); break;

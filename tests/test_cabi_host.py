@@ -113,7 +113,8 @@ def test_probe_streams_argument_errors(L):
     r = (ctypes.c_void_p * 3)(A, A + 0x100000, A + 0x200000)
     w = (ctypes.c_void_p * 3)(A + 0x300000, A + 0x400000, A + 0x500000)
     S = A + 0x600000
-    assert f(r, 4, w, 1, 1024, S, None) == ERR_PARAM
+    assert f(r, 18, w, 1, 1024, S, None) == ERR_PARAM
+    assert f(r, 1, w, 4, 1024, S, None) == ERR_PARAM
     assert f(r, 0, w, 0, 1024, S, None) == ERR_PARAM
     assert f(None, 1, w, 1, 1024, S, None) == ERR_NULL
     assert f(r, 2, w, 0, 1024, None, None) == ERR_NULL            # read-only needs the sink

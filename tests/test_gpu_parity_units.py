@@ -141,8 +141,8 @@ def test_probe_streams_moves_what_it_says(B):
     nothing outside the buffers is touched, a read-only run writes nothing."""
     rng = np.random.default_rng(3500)
     n = 256 * 37
-    reads = [torch.from_numpy(rng.normal(0, 1, n).astype(np.float32)).cuda() for _ in range(3)]
-    for R in range(0, 4):
+    reads = [torch.from_numpy(rng.normal(0, 1, n).astype(np.float32)).cuda() for _ in range(17)]
+    for R in (0, 1, 2, 3, 4, 9, 17):
         for W in range(0, 4):
             if R + W == 0:
                 continue
