@@ -57,13 +57,18 @@ def _sample_blocks(cfg, rng, nblocks, blen):
     return out
 
 
-def _run(P, oracle, cfg, dense, steps, blocks, fused=True, self_rank=0, check_peers=True, shadow=False):
+def _run(P, oracle, cfg, dense, steps, blocks, fused=True, self_rank=0, check_peers=True, shadow=False,
+         wl_kwargs=None, max_workgroups=0, static=False):
     """Steps the workload on the GPU and the oracle on the blocks; compares after every step.
 
     shadow=True keeps a second copy of the observed worker's state that is stepped with the
-    three single-tensor calls, and requires whole-arena bit equality with the fused state."""
+    three single-tensor calls, and requires whole-arena bit equality with the fused state.
+    wl_kwargs: forms of the workload (peers in the sparse form, 16-bit gradients, peers' gradients
+    resident so that correction passes sum in the kernel); max_workgroups: bounded grids;
+    static: the pass goes through cdsgd_step_fused_static instead of the plan."""
     pkg, runner, synth = P
-    wl = runner.Workload(cfg, dense=dense, self_rank=self_rank)
+    wl = runner.Workload(cfg, dense=dense, self_rank=self_rank, **(wl_kwargs or {}))
+    wl.plan.set_max_workgroups(max_workgroups)
     sh = None
     if shadow:
         sh = dict(w_global=wl.w_global.clone(), w_local=wl.w_local.clone(), residual=wl.residual.clone(),
@@ -78,7 +83,10 @@ def _run(P, oracle, cfg, dense, steps, blocks, fused=True, self_rank=0, check_pe
         cap = wl.prepare_step(s, capture=blocks)
         comp = wl.compressed(s)
         r_old = wl.residual.clone() if (comp and shadow) else None
-        if fused:
+        if static:
+            pkg.binding.cdsgd_step_fused_static(wl._plan_tensors(), wl._plan_peers(), N, self_rank, s, cfg.k, t,
+                                                cfg.lr, cfg.lr)
+        elif fused:
             wl.fused_step(s)
         else:
             wl.unfused_step(s)
@@ -205,4 +213,42 @@ def test_c5_flat_bucket_full_size_sampled(P, oracle):
     # all 10 iterations: one correction, nine compressed
     nz, tot = _run(P, oracle, cfg, False, cfg.iterations, blocks, shadow=True)
     # first compressed step fires with probability exp(-2.5); later ones a little more
+    assert 0.05 * tot < nz < 0.25 * tot
+
+
+VARIANTS = {
+    "sparse_peers": dict(wl_kwargs=dict(sparse_peers=True), shadow=True),
+    "bf16_gradients": dict(wl_kwargs=dict(grad_dtype=torch.bfloat16)),
+    "fp16_gradients": dict(wl_kwargs=dict(grad_dtype=torch.float16)),
+    "sum_in_kernel": dict(wl_kwargs=dict(full_grads=True), shadow=True),
+    "bounded_grid": dict(max_workgroups=1024, shadow=True),
+    "no_alloc_entry": dict(static=True, shadow=True),
+}
+
+
+@pytest.mark.parametrize("variant", sorted(VARIANTS))
+def test_c4_vgg16_full_size_other_forms(P, oracle, variant):
+    """The other forms of the pass that the benchmark times on the VGG-16-shaped list, at that size:
+    sampled blocks against the oracle after every iteration (two correction passes, eight compressed
+    ones, dense recipe), and, where the gradients are fp32, the whole arena against the three
+    single-tensor calls."""
+    cfg = P[2].config("c4_vgg16")
+    rng = np.random.default_rng(4400 + sorted(VARIANTS).index(variant))
+    blocks = _sample_blocks(cfg, rng, 12, 1 << 13)
+    nz, tot = _run(P, oracle, cfg, True, 10, blocks, **VARIANTS[variant])
+    assert nz > 0.2 * tot
+
+
+@pytest.mark.parametrize("variant", ["no_alloc_entry", "sparse_peers"])
+def test_c5_flat_bucket_full_size_other_forms(P, oracle, variant):
+    """The 4 GiB bucket (2^30 elements in one tensor, chain form of the decode) through the entry point
+    that allocates nothing (262,144 chunks in its static table) and with the peers' streams in the
+    sparse form: first, last and random blocks against the oracle, whole arena against the three calls."""
+    cfg = P[2].config("c5_flat4g")
+    rng = np.random.default_rng(5500 + len(variant))
+    n = cfg.sizes[0]
+    blocks = [(0, 0, 1 << 14), (0, n - (1 << 14), 1 << 14), (0, (1 << 29) - 4096, 8192)]
+    for _ in range(13):
+        blocks.append((0, int(rng.integers(0, n // 16 - 1024)) * 16, 1 << 14))
+    nz, tot = _run(P, oracle, cfg, False, 4, blocks, **VARIANTS[variant])
     assert 0.05 * tot < nz < 0.25 * tot
