@@ -237,6 +237,40 @@ def time_small(name, steps=200):
             "note": "one period of k steps (1 correction + k-1 compressed) per graph; wall clock incl. launch"}
 
 
+def layer_by_layer(name, steps, min_seconds=0.3):
+    """The compressed pass enqueued layer by layer, last layer first, as back-propagation would deliver
+    the gradients (Sec. 3.2.2), against the one-launch pass over the whole list: one range per tensor,
+    and ranges grouped into buckets of at least 4 Mi elements.  ms per iteration of the whole list."""
+    import torch
+    from paper_2106_10796_amd import runner, synth
+    cfg = synth.config(name)
+    wl = runner.Workload(cfg)
+    wl.prepare_step(1)
+    wl.peer_residual = [None] * cfg.num_workers
+    wl._scratch = None
+    torch.cuda.empty_cache()
+    stream = torch.cuda.current_stream()
+    T, c = cfg.num_tensors, cfg
+    buckets, hi, acc = [], T, 0
+    for i in range(T - 1, -1, -1):
+        acc += cfg.sizes[i]
+        if acc >= (4 << 20) or i == 0:
+            buckets.append((i, hi - i))
+            hi, acc = i, 0
+    forms = {"whole_list_one_launch": lambda: wl.plan.step(1, c.k, c.threshold, c.lr, c.lr),
+             "one_range_per_tensor": lambda: [wl.plan.step_range(i, 1, 1, c.k, c.threshold, c.lr, c.lr)
+                                              for i in range(T - 1, -1, -1)],
+             "buckets_of_4Mi_elements": lambda: [wl.plan.step_range(lo, cnt, 1, c.k, c.threshold, c.lr, c.lr)
+                                                 for lo, cnt in buckets]}
+    out = {"workload": name, "tensors": T, "buckets": len(buckets)}
+    for tag, fn in forms.items():
+        fn()
+        b = timed_blocks(lambda: [fn() for _ in range(steps)], steps, stream, min_seconds=min_seconds, min_blocks=5)
+        out["ms_" + tag] = b["median_ms_per_step"]
+    wl.destroy()
+    return out
+
+
 def time_correction_sum(name, steps, warmup, min_seconds=0.5):
     """Correction pass that sums the N workers' fp32 gradients in the kernel (Alg. 1, else-branch):
     reads W and N gradients, writes W and W_loc = 12 + 4N bytes per element."""
@@ -523,6 +557,9 @@ def main():
     ap.add_argument("--only-correction-sum", action="store_true",
                     help="time only the correction pass that sums the N gradients in the kernel (for profiling "
                          "k_fused_full<true, ...> on its own) and print its figures instead of the benchmark line")
+    ap.add_argument("--only-layer-by-layer", action="store_true",
+                    help="time only the compressed pass enqueued layer by layer (cdsgd_step_fused_range) against the "
+                         "one-launch pass and print those figures instead of the benchmark line")
     ap.add_argument("--only-overlap", action="store_true",
                     help="run only the overlap demo (split step on two streams beside a forward stand-in) and print "
                          "its figures instead of the benchmark line")
@@ -554,6 +591,9 @@ def main():
     if args.only_overlap:
         print(json.dumps(overlap_demo(args.workload)))
         return 0
+    if args.only_layer_by_layer:
+        print(json.dumps(layer_by_layer(args.workload, max(5, args.steps // 4))))
+        return 0
     if args.only_correction_sum:
         r = time_correction_sum(args.workload, args.steps, args.warmup, min_seconds=min(0.5, args.min_seconds))
         r["workload"] = args.workload
@@ -580,6 +620,9 @@ def main():
         torch.cuda.empty_cache()
         for name in ("c1_single", "c2_resnet20"):
             extra[name] = time_small(name)
+        for name in ("c3_resnet50", "c4_vgg16"):
+            extra["layer_by_layer_" + name] = layer_by_layer(name, max(5, args.steps // 4))
+            torch.cuda.empty_cache()
         r, w = time_workload(args.workload, max(5, args.steps // 2), max(2, args.warmup // 2),
                              want_correction=False, grad_dtype=torch.bfloat16, min_seconds=0.5)
         w.destroy()

@@ -211,6 +211,25 @@ int cdsgd_step_global(cdsgd_plan *plan, long step, int k, float threshold, float
                       void *hip_stream);
 
 /*
+ * Layer-by-layer form of the three passes above (Sec. 3.2.2: quantisation and communication
+ * proceed layer by layer, a layer's turn coming when back-propagation has produced its
+ * gradient): the same pass over tensors [first_tensor, first_tensor + num_tensors) of the
+ * plan's layer list only.  Nothing of any other tensor is read or written.  Every tensor of the
+ * list stepped exactly once with the same `step`, in any order and any grouping, leaves bit for
+ * bit what the whole-list call leaves.  The caller keeps `step` the same for all ranges of one
+ * iteration; the peers' streams (or agg_full, or the bound gradients) of a range must be in place
+ * when its call is enqueued.
+ *   errors      those of the whole-list call; CDSGD_ERR_PARAM for first_tensor < 0,
+ *               num_tensors < 1 or a range that passes the end of the list.
+ */
+int cdsgd_step_fused_range(cdsgd_plan *plan, int first_tensor, int num_tensors, long step, int k,
+                           float threshold, float lr_local, float lr_global, void *hip_stream);
+int cdsgd_step_local_range(cdsgd_plan *plan, int first_tensor, int num_tensors, float lr_local,
+                           void *hip_stream);
+int cdsgd_step_global_range(cdsgd_plan *plan, int first_tensor, int num_tensors, long step, int k,
+                            float threshold, float lr_global, void *hip_stream);
+
+/*
  * Sparse form of a packed stream: a wire format of THIS LIBRARY, not of the paper, which names a
  * combination with sparsification as future work (Sec. 7) and defines nothing; Sec. 2.3 observes
  * that residuals stay below the threshold for long stretches, i.e. that most packed words are zero.

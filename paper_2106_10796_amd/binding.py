@@ -102,6 +102,12 @@ def lib():
         L.cdsgd_step_local.argtypes = [vp, f, vp]
         L.cdsgd_step_global.restype = i
         L.cdsgd_step_global.argtypes = [vp, ctypes.c_long, i, f, f, vp]
+        L.cdsgd_step_fused_range.restype = i
+        L.cdsgd_step_fused_range.argtypes = [vp, i, i, ctypes.c_long, i, f, f, f, vp]
+        L.cdsgd_step_local_range.restype = i
+        L.cdsgd_step_local_range.argtypes = [vp, i, i, f, vp]
+        L.cdsgd_step_global_range.restype = i
+        L.cdsgd_step_global_range.argtypes = [vp, i, i, ctypes.c_long, i, f, f, vp]
         L.cdsgd_plan_bind_full_grads.restype = i
         L.cdsgd_plan_bind_full_grads.argtypes = [vp, ctypes.POINTER(ctypes.POINTER(vp))]
         L.cdsgd_step_warmup.restype = i
@@ -347,6 +353,21 @@ class Plan:
     def step_global(self, step, k, threshold, lr_global):
         st = lib().cdsgd_step_global(self._handle, int(step), int(k), float(threshold), float(lr_global), _stream())
         _check(st, "cdsgd_step_global")
+
+    def step_range(self, first_tensor, num_tensors, step, k, threshold, lr_local, lr_global):
+        """The fused pass over tensors [first_tensor, first_tensor + num_tensors) only (cdsgd_step_fused_range)."""
+        st = lib().cdsgd_step_fused_range(self._handle, int(first_tensor), int(num_tensors), int(step), int(k),
+                                          float(threshold), float(lr_local), float(lr_global), _stream())
+        _check(st, "cdsgd_step_fused_range")
+
+    def step_local_range(self, first_tensor, num_tensors, lr_local):
+        st = lib().cdsgd_step_local_range(self._handle, int(first_tensor), int(num_tensors), float(lr_local), _stream())
+        _check(st, "cdsgd_step_local_range")
+
+    def step_global_range(self, first_tensor, num_tensors, step, k, threshold, lr_global):
+        st = lib().cdsgd_step_global_range(self._handle, int(first_tensor), int(num_tensors), int(step), int(k),
+                                           float(threshold), float(lr_global), _stream())
+        _check(st, "cdsgd_step_global_range")
 
     def bind_full_grads(self, peer_grads):
         """peer_grads[j][i]: worker j's fp32 gradient of tensor i; entry self_rank may be None

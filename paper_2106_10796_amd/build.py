@@ -36,7 +36,10 @@ def source_id(extra_flags=()) -> str:
     It is compiled into the library (cdsgd_build_id) so that a library can be matched to the tree."""
     h = hashlib.sha256()
     headers = sorted(os.path.join(INCLUDE, f) for f in os.listdir(INCLUDE) if f.endswith(".h"))
-    for path in [SRC, *SRC_HOST, *headers]:
+    csrc = os.path.dirname(SRC)                       # cdsgd.hip includes the kernels' .hpp files beside it
+    sources = sorted(os.path.join(csrc, f) for f in os.listdir(csrc) if f.endswith((".hip", ".hpp", ".cpp")))
+    assert SRC in sources and all(p in sources for p in SRC_HOST)
+    for path in [*sources, *headers]:
         h.update(os.path.basename(path).encode() + b"\0")
         with open(path, "rb") as fh:
             h.update(fh.read())

@@ -1,0 +1,254 @@
+// Single-tensor kernels: quantise-and-pack (a1-a3), decode-and-sum (a4), update (a5, a6).
+#pragma once
+
+namespace {
+
+// ---------------------------------------------------------------------------
+// a4: decode-and-sum (Sec. 3.2.1; sum of eq. 10)
+// ---------------------------------------------------------------------------
+// A lane keeps the packed bytes of its kQpl quads of one worker in one
+// register: byte j = quad j.
+
+// Bytes of one worker for this lane's quads.
+template <bool G>
+__device__ __forceinline__ unsigned load_codes(const uint8_t *stream, unsigned tid, unsigned rem_bytes)
+{
+    unsigned w = 0;
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) {
+        const unsigned qi = j * kBlock + tid;
+        unsigned b = 0;
+#if CDSGD_NT_CODES
+        if (!G || qi < rem_bytes) b = __builtin_nontemporal_load(stream + qi);
+#else
+        if (!G || qi < rem_bytes) b = stream[qi];
+#endif
+        w |= b << (8 * j);
+    }
+    return w;
+}
+
+// Literal fp32 chain: agg += value(code) for the 4*kQpl elements of this lane,
+// one rounded add per element.  The codes are first rewritten, 16 at a time,
+// as 2-bit two's-complement counts (01 -> +1, 10 -> -1, 00 and 11 -> 0) so
+// that one signed bit-field extract yields the multiplier.
+__device__ __forceinline__ void chain_codes(f4 (&agg)[kQpl], unsigned w, float t)
+{
+    const unsigned x = w & 0x55555555u;
+    const unsigned y = (w >> 1) & 0x55555555u;
+    const unsigned lo = x ^ y;
+    const unsigned hi = y & ~x;
+    const unsigned s = lo | (hi << 1);
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) {
+#pragma unroll
+        for (unsigned c = 0; c < 4; ++c) {
+            const int m = ((int)(s << (30u - (8u * j + 2u * c)))) >> 30;
+            agg[j][c] = __builtin_fmaf((float)m, t, agg[j][c]);
+        }
+    }
+}
+
+// Count form for thresholds that are powers of two (every partial sum of the
+// chain is then exact, so sum == count * t bit for bit).  Per worker the 16
+// codes become biased counts (2 + value) in 2-bit fields without borrows, and
+// are added into four registers of byte-wide fields: acc[c] byte j belongs to
+// element c of quad j.
+__device__ __forceinline__ void count_codes(unsigned (&acc)[4], unsigned w)
+{
+    const unsigned z = ((w & 0x55555555u) | 0xAAAAAAAAu) - ((w >> 1) & 0x55555555u);
+    acc[0] += z & 0x03030303u;
+    acc[1] += (z >> 2) & 0x03030303u;
+    acc[2] += (z >> 4) & 0x03030303u;
+    acc[3] += (z >> 6) & 0x03030303u;
+}
+
+// acc holds 2*num_summed + sum of values; bias_t = -(2*num_summed)*t.
+__device__ __forceinline__ void counts_to_sum(f4 (&agg)[kQpl], const unsigned (&acc)[4], float t,
+                                              float bias_t)
+{
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) {
+#pragma unroll
+        for (unsigned c = 0; c < 4; ++c) {
+            const float cnt = (float)((acc[c] >> (8u * j)) & 0xFFu);
+            agg[j][c] = __builtin_fmaf(cnt, t, bias_t);
+        }
+    }
+}
+
+// Sum workers [p_begin, p_end) of a pointer table into agg (chain) or acc (count),
+// kPeerBatch streams in flight at a time.
+template <bool G, bool POW2>
+__device__ __forceinline__ void sum_streams(f4 (&agg)[kQpl], unsigned (&acc)[4],
+                                            const uint8_t *const *__restrict__ tab, int p_begin,
+                                            int p_end, size_t quad0, unsigned tid,
+                                            unsigned rem_bytes, float t)
+{
+    int p = p_begin;
+    for (; p + kPeerBatch <= p_end; p += kPeerBatch) {
+        unsigned w[kPeerBatch];
+#pragma unroll
+        for (int i = 0; i < kPeerBatch; ++i) w[i] = load_codes<G>(tab[p + i] + quad0, tid, rem_bytes);
+#pragma unroll
+        for (int i = 0; i < kPeerBatch; ++i) {
+            if (POW2) count_codes(acc, w[i]);
+            else chain_codes(agg, w[i], t);
+        }
+    }
+    if (kPeerBatch > 4 && p + 4 <= p_end) {
+        unsigned w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = load_codes<G>(tab[p + i] + quad0, tid, rem_bytes);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (POW2) count_codes(acc, w[i]);
+            else chain_codes(agg, w[i], t);
+        }
+        p += 4;
+    }
+    for (; p < p_end; ++p) {
+        const unsigned w = load_codes<G>(tab[p] + quad0, tid, rem_bytes);
+        if (POW2) count_codes(acc, w);
+        else chain_codes(agg, w, t);
+    }
+}
+
+
+
+// a4 for one tensor; the worker pointers travel in the kernel arguments.
+struct StreamTable {
+    const uint8_t *p[CDSGD_MAX_WORKERS];
+};
+
+template <bool G, bool POW2>
+__device__ __forceinline__ void decode_sum_chunk(const StreamTable &tab, int num_workers,
+                                                 float *__restrict__ agg_out, size_t quad0,
+                                                 unsigned rem_elems, unsigned rem_bytes, float t,
+                                                 float bias_t)
+{
+    const unsigned tid = threadIdx.x;
+    f4 agg[kQpl];
+    unsigned acc[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) agg[j] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+    sum_streams<G, POW2>(agg, acc, tab.p, 0, num_workers, quad0, tid, rem_bytes, t);
+    if (POW2) counts_to_sum(agg, acc, t, bias_t);
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) {
+        const unsigned qi = j * kBlock + tid;
+        st4g<G>(agg_out, qi, quad_count<G>(rem_elems, qi), agg[j]);
+    }
+}
+
+template <bool POW2>
+__global__ __launch_bounds__(CDSGD_BLOCK) void k_decode_sum(StreamTable tab, int num_workers,
+                                                            float *__restrict__ agg, Extent ext, float t,
+                                                            float bias_t)
+{
+    const unsigned chunk = blockIdx.x;
+    const size_t quad0 = (size_t)chunk * kChunkQuads;
+    agg += 4 * quad0;
+    if (chunk < ext.full_chunks)
+        decode_sum_chunk<false, POW2>(tab, num_workers, agg, quad0, kChunkElems, kChunkQuads, t, bias_t);
+    else
+        decode_sum_chunk<true, POW2>(tab, num_workers, agg, quad0, ext.tail_elems, ext.tail_bytes, t, bias_t);
+}
+
+// a5 + a6 (eq. 10, eq. 11), both from the weight that was loaded.
+template <bool G, bool LOCAL, bool GLOBAL, int GT = kGradF32>
+__device__ __forceinline__ void update_chunk(float *__restrict__ wg, float *__restrict__ wl,
+                                             const void *__restrict__ grad,
+                                             const float *__restrict__ agg, unsigned rem_elems,
+                                             float lr_local, float scale)
+{
+    const unsigned tid = threadIdx.x;
+    f4 w[kQpl], g[kQpl], a[kQpl];
+    int cnt[kQpl];
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) {
+        const unsigned qi = j * kBlock + tid;
+        cnt[j] = quad_count<G>(rem_elems, qi);
+        w[j] = ld4g<G>(wg, qi, cnt[j]);
+        if (LOCAL) g[j] = ldgrad<G, GT>(grad, qi, cnt[j]);
+        if (GLOBAL) a[j] = ld4g<G>(agg, qi, cnt[j]);
+    }
+#pragma unroll
+    for (unsigned j = 0; j < kQpl; ++j) {
+        const unsigned qi = j * kBlock + tid;
+        if (LOCAL) {
+            f4 v;
+#pragma unroll
+            for (unsigned c = 0; c < 4; ++c) v[c] = __builtin_fmaf(-lr_local, g[j][c], w[j][c]);
+            st4g<G>(wl, qi, cnt[j], v);
+        }
+        if (GLOBAL) {
+            f4 v;
+#pragma unroll
+            for (unsigned c = 0; c < 4; ++c) v[c] = __builtin_fmaf(-scale, a[j][c], w[j][c]);
+            st4g<G>(wg, qi, cnt[j], v);
+        }
+    }
+}
+
+template <bool LOCAL, bool GLOBAL>
+__global__ __launch_bounds__(CDSGD_BLOCK) void k_update(float *__restrict__ wg, float *__restrict__ wl,
+                                                        const float *__restrict__ grad,
+                                                        const float *__restrict__ agg, Extent ext,
+                                                        float lr_local, float scale)
+{
+    const unsigned chunk = blockIdx.x;
+    const size_t quad0 = (size_t)chunk * kChunkQuads;
+    wg += 4 * quad0;
+    if (LOCAL) {
+        wl += 4 * quad0;
+        grad += 4 * quad0;
+    }
+    if (GLOBAL) agg += 4 * quad0;
+    if (chunk < ext.full_chunks) update_chunk<false, LOCAL, GLOBAL>(wg, wl, grad, agg, kChunkElems, lr_local, scale);
+    else update_chunk<true, LOCAL, GLOBAL>(wg, wl, grad, agg, ext.tail_elems, lr_local, scale);
+}
+
+typedef unsigned u4 __attribute__((ext_vector_type(4)));
+
+// values of the codes of a register, as 2-bit two's-complement fields (01 -> +1, 10 -> -1, else 0)
+__device__ __forceinline__ unsigned signed_fields(unsigned w)
+{
+    const unsigned x = w & 0x55555555u;
+    const unsigned y = (w >> 1) & 0x55555555u;
+    return (x ^ y) | ((y & ~x) << 1);
+}
+
+
+
+// a1-a3 for one tensor, one wave per piece of L = 64 quads (measured: 6.68 TB/s against 6.41 TB/s for
+// 512-lane workgroups with two quads per lane; the other two single-tensor kernels are faster in that
+// shape and keep it).  `ext` describes the tensor in pieces: full_chunks whole pieces, then at most one
+// ragged piece of tail_elems elements and tail_bytes packed bytes.
+template <unsigned L>
+__global__ __launch_bounds__(L) void k_quantize_pack(const float *__restrict__ grad, float *__restrict__ resid,
+                                                       uint8_t *__restrict__ packed, Extent ext, float t)
+{
+    const unsigned piece = blockIdx.x, lane = threadIdx.x;
+    const size_t quad0 = (size_t)piece * L;
+    grad += 4 * quad0;
+    resid += 4 * quad0;
+    packed += quad0;
+    f4 sent;
+    if (piece < ext.full_chunks) {
+        const f4 g = ld4(grad, lane);
+        f4 r = ld4(resid, lane);
+        const unsigned b = quantize_quad(g, r, t, sent);
+        st4(resid, lane, r);
+        packed[lane] = (uint8_t)b;
+    } else {
+        const int cnt = quad_count<true>(ext.tail_elems, lane);
+        const f4 g = ld4g<true>(grad, lane, cnt);
+        f4 r = ld4g<true>(resid, lane, cnt);
+        const unsigned b = quantize_quad(g, r, t, sent);
+        st4g<true>(resid, lane, cnt, r);
+        if (lane < ext.tail_bytes) packed[lane] = (uint8_t)b;
+    }
+}
+
+}  // namespace

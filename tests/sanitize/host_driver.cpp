@@ -69,6 +69,9 @@ int main()
     bad += cdsgd_decode_sum_sparse(two, 2, A, 16, 0.5f, nullptr) != CDSGD_ERR_NULL;
     bad += cdsgd_plan_set_peer_format(nullptr, CDSGD_PEERS_SPARSE) != CDSGD_ERR_NULL;
     bad += cdsgd_plan_set_max_workgroups(nullptr, 1) != CDSGD_ERR_NULL;
+    bad += cdsgd_step_fused_range(nullptr, 0, 1, 1, 4, 0.5f, 0.1f, 0.1f, nullptr) != CDSGD_ERR_NULL;
+    bad += cdsgd_step_local_range(nullptr, 0, 1, 0.1f, nullptr) != CDSGD_ERR_NULL;
+    bad += cdsgd_step_global_range(nullptr, 0, 1, 1, 4, 0.5f, 0.1f, nullptr) != CDSGD_ERR_NULL;
     {
         const float *rd[3] = {A, A + 4096, A + 8192};
         float *wr[3] = {A + 12288, A + 16384, A + 12288 + 4};

@@ -33,7 +33,8 @@ def test_header_declares_the_named_entry_points():
                  "cdsgd_step_local", "cdsgd_step_global", "cdsgd_cost_iteration", "cdsgd_cost_period_mean",
                  "cdsgd_plan_create_typed", "cdsgd_plan_set_thresholds", "cdsgd_plan_set_max_workgroups",
                  "cdsgd_step_fused_static", "cdsgd_build_id", "cdsgd_sparse_encode", "cdsgd_decode_sum_sparse",
-                 "cdsgd_sparse_words", "cdsgd_sparse_segments", "cdsgd_plan_set_peer_format", "cdsgd_probe_streams"):
+                 "cdsgd_sparse_words", "cdsgd_sparse_segments", "cdsgd_plan_set_peer_format", "cdsgd_probe_streams",
+                 "cdsgd_step_fused_range", "cdsgd_step_local_range", "cdsgd_step_global_range"):
         assert must in names
 
 
@@ -226,6 +227,9 @@ def test_plan_and_step_argument_errors(L):
     step = L.cdsgd_step_fused
     assert step(None, 1, 4, 0.5, 0.1, 0.1, None) == ERR_NULL
     assert L.cdsgd_plan_set_max_workgroups(None, 4) == ERR_NULL
+    assert L.cdsgd_step_fused_range(None, 0, 1, 1, 4, 0.5, 0.1, 0.1, None) == ERR_NULL
+    assert L.cdsgd_step_local_range(None, 0, 1, 0.1, None) == ERR_NULL
+    assert L.cdsgd_step_global_range(None, 0, 1, 1, 4, 0.5, 0.1, None) == ERR_NULL
     assert L.cdsgd_plan_destroy(None) == OK
     fake = ctypes.c_void_p(A)  # parameter checks come before the plan is looked at
     assert step(fake, 1, 0, 0.5, 0.1, 0.1, None) == ERR_PARAM

@@ -159,8 +159,9 @@ def test_probe_streams_moves_what_it_says(B):
             assert bool((sink == 7.0).all())
 
 
-def _run_layer_list(B, oracle, sizes, N, self_rank, k, t, steps, seed, lr_l=0.4, lr_g=0.1):
-    """Fused step vs oracle vs the three-call composition on an arbitrary layer list."""
+def _run_layer_list(B, oracle, sizes, N, self_rank, k, t, steps, seed, lr_l=0.4, lr_g=0.1, stepper=None):
+    """Fused step vs oracle vs the three-call composition on an arbitrary layer list.
+    stepper(plan, s): how iteration s is enqueued (default: one cdsgd_step_fused over the list)."""
     rng = np.random.default_rng(seed)
     T = len(sizes)
     dev = dict(device="cuda")
@@ -199,7 +200,10 @@ def _run_layer_list(B, oracle, sizes, N, self_rank, k, t, steps, seed, lr_l=0.4,
             sims[i]._last = (comp, agg, words)
         resid_before = [r.clone() for r in state[0]["residual"]]
         packed_before = [p.clone() for p in state[0]["packed_self"]]
-        plan.step(s, k, t, lr_l, lr_g)
+        if stepper is None:
+            plan.step(s, k, t, lr_l, lr_g)
+        else:
+            stepper(plan, s)
         # composition on the second copy
         c = state[1]
         for i in range(T):
@@ -233,6 +237,65 @@ def _run_layer_list(B, oracle, sizes, N, self_rank, k, t, steps, seed, lr_l=0.4,
 
 
 RAGGED = [1, 10, 16, 17, 64, 100, 1000, 4095, 4096, 4097, 9000, 36864, 5, 20011]
+
+
+@pytest.mark.parametrize("N,t,split", [(4, 0.5, False), (16, 0.05, False), (9, 0.25, True), (2, 0.3, True)])
+def test_layer_by_layer_equals_whole_list(B, oracle, N, t, split):
+    """The list stepped in ranges, last layers first as back-propagation delivers them, in groups of
+    uneven size (Sec. 3.2.2): oracle, three-call composition and untouched outputs as for the whole list."""
+    k, lr_l, lr_g = 3, 0.4, 0.1
+    T = len(RAGGED)
+    cuts = [T, 13, 12, 8, 7, 3, 0]                   # groups [13,14) [12,13) [8,12) [7,8) [3,7) [0,3)
+
+    def stepper(plan, s):
+        for hi, lo in zip(cuts[:-1], cuts[1:]):
+            if split:
+                plan.step_local_range(lo, hi - lo, lr_l)
+                plan.step_global_range(lo, hi - lo, s, k, t, lr_g)
+            else:
+                plan.step_range(lo, hi - lo, s, k, t, lr_l, lr_g)
+
+    _run_layer_list(B, oracle, RAGGED, N, N // 2, k, t, 5, 3600 + N, lr_l, lr_g, stepper=stepper)
+
+
+def test_a_range_touches_only_its_tensors(B):
+    sizes = [5000, 17, 4096, 9000, 300]
+    rng = np.random.default_rng(3700)
+    dev = dict(device="cuda")
+    N, self_rank = 3, 1
+    keys = ("w_global", "w_local", "residual", "packed_self")
+    st = dict(w_global=[torch.from_numpy(rng.normal(0, 0.3, n).astype(np.float32)).cuda() for n in sizes],
+              w_local=[torch.full((n,), 9.0, **dev) for n in sizes],
+              residual=[torch.from_numpy(rng.normal(0, 0.3, n).astype(np.float32)).cuda() for n in sizes],
+              grad=[torch.from_numpy(rng.normal(0, 0.5, n).astype(np.float32)).cuda() for n in sizes],
+              packed_self=[torch.full((B.packed_words(n),), -1, dtype=torch.int32, **dev) for n in sizes],
+              agg_full=[torch.from_numpy(rng.normal(0, 0.5, n).astype(np.float32)).cuda() for n in sizes])
+    peers = [None if j == self_rank else
+             [torch.from_numpy(rng.integers(0, 2**32, B.packed_words(n), dtype=np.uint32).view(np.int32)).cuda()
+              for n in sizes] for j in range(N)]
+    plan = B.Plan([{key: st[key][i] for key in st} for i in range(len(sizes))], peers, N, self_rank)
+    for step in (1, 0):                                # a compressed pass, then a correction pass
+        before = {key: [v.clone() for v in st[key]] for key in keys}
+        plan.step_range(1, 3, step, 2, 0.5, 0.4, 0.1)
+        torch.cuda.synchronize()
+        for i in range(len(sizes)):
+            inside = 1 <= i < 4
+            for key in keys:
+                same = torch.equal(st[key][i].view(torch.int32), before[key][i].view(torch.int32))
+                if not inside:
+                    assert same, "%s of tensor %d outside the range was written (step %d)" % (key, i, step)
+                elif key in ("w_global", "w_local"):
+                    assert not same, "%s of tensor %d inside the range was not stepped (step %d)" % (key, i, step)
+    for first, count in ((-1, 2), (0, 0), (3, 3), (5, 1), (0, 6)):
+        with pytest.raises(RuntimeError):
+            plan.step_range(first, count, 1, 2, 0.5, 0.4, 0.1)
+        with pytest.raises(RuntimeError):
+            plan.step_local_range(first, count, 0.4)
+        with pytest.raises(RuntimeError):
+            plan.step_global_range(first, count, 1, 2, 0.5, 0.1)
+    plan.step_range(0, 5, 1, 2, 0.5, 0.4, 0.1)         # the whole list as one range is fine
+    torch.cuda.synchronize()
+    plan.destroy()
 
 
 @pytest.mark.parametrize("t", [0.5, 0.05])
@@ -333,7 +396,8 @@ def test_fused_step_many_tiny_tensors(B, oracle):
 
 def test_fused_step_random_configurations(B, oracle):
     """Seeded random layer lists, worker counts, positions, periods and thresholds (both decode
-    forms), each checked step by step against the oracle and the three-call composition.
+    forms), each checked step by step against the oracle and the three-call composition; every
+    third case steps the list as ranges of tensors in a random order.
     CDSGD_FUZZ_CASES raises the number of cases for a longer soak."""
     import os
     cases = int(os.environ.get("CDSGD_FUZZ_CASES", "40"))
@@ -355,10 +419,22 @@ def test_fused_step_random_configurations(B, oracle):
         self_rank = int(rng.integers(0, N))
         k = int(rng.integers(1, 5))
         t = float(rng.choice([0.5, 0.25, 2.0, 0.05, 0.3, 1e-3, 0.0625, 7.0]))
+        stepper, groups = None, None
+        if case % 3 == 2:
+            # every third case enqueues the list as ranges: a random partition, in a random order
+            r2 = np.random.default_rng(5150 + case)
+            cuts = sorted(set([0, T] + [int(x) for x in r2.integers(0, T + 1, int(r2.integers(0, 4)))]))
+            groups = [(lo, hi - lo) for lo, hi in zip(cuts[:-1], cuts[1:])]
+            groups = [groups[i] for i in r2.permutation(len(groups))]
+
+            def stepper(plan, s, groups=groups, k=k, t=t):
+                for lo, cnt in groups:
+                    plan.step_range(lo, cnt, s, k, t, 0.4, 0.1)
         try:
             _run_layer_list(B, oracle, sizes, N, self_rank, k=k, t=t, steps=int(rng.integers(2, 5)),
-                            seed=9000 + case)
+                            seed=9000 + case, stepper=stepper)
         except AssertionError as e:
-            raise AssertionError("case %d: sizes=%s N=%d self=%d k=%d t=%g: %s" % (case, sizes, N, self_rank, k, t, e))
+            raise AssertionError("case %d: sizes=%s N=%d self=%d k=%d t=%g ranges=%s: %s"
+                                 % (case, sizes, N, self_rank, k, t, groups, e))
         if cases > 100 and case % 100 == 99:
             print("fuzz: %d cases done" % (case + 1), flush=True)
