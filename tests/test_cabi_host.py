@@ -372,3 +372,21 @@ def test_product_does_not_import_the_oracle():
         for f in files:
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 assert not pat.search(open(os.path.join(dirpath, f)).read()), f
+
+
+def test_native_client_builds_and_needs_a_gpu():
+    """The C++ client of the ABI (tests/native/abi_client.cpp) compiles against the header and links the
+    library with the host compiler alone; without a GPU it stops at its first HIP call, before any call
+    into the library."""
+    import importlib.util
+    import subprocess
+    spec = importlib.util.spec_from_file_location("native_client_build", os.path.join(ROOT, "tests", "native", "build.py"))
+    native = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(native)
+    exe = native.ensure_built()
+    assert os.access(exe, os.X_OK)
+    import torch
+    if torch.cuda.is_available():
+        return
+    r = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=60)
+    assert r.returncode == 2 and "abi client ok" not in r.stdout
