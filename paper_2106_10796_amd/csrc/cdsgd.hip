@@ -20,9 +20,9 @@
 //     lane: 256-lane workgroups for the compressed pass (the peers' codes
 //     come in through LDS, 128 bits per lane and 16 peers per instruction),
 //     single waves for the passes on 32-bit gradients.
-//   * Of the single-tensor kernels, decode-and-sum and the update give a chunk
-//     to a workgroup of kBlock lanes, lane `tid` taking quads j*kBlock + tid;
-//     quantise-and-pack works in single-wave pieces.
+//   * Of the single-tensor kernels, decode-and-sum gives a chunk to a
+//     workgroup of kBlock lanes, lane `tid` taking quads j*kBlock + tid;
+//     quantise-and-pack and the update work in single-wave pieces.
 // Either way every wave instruction on an fp32 buffer touches one contiguous
 // 1 KiB span: all traffic is fully coalesced.
 //
@@ -115,7 +115,8 @@ inline Extent extent_of_units(size_t n, unsigned unit_quads)
 // Most chunks (or segments) a tensor or a layer list may have: a launch of one workgroup of up to
 // 1024 lanes per chunk stays below 2^32 threads (1.7e10 elements).
 constexpr unsigned long long kMaxGrid = 0xFFFFFFFFull / 1024;
-constexpr unsigned kQuantLanes = 64;  // lanes = quads of a piece of k_quantize_pack
+constexpr unsigned kQuantLanes = 64;   // lanes = quads of a piece of k_quantize_pack
+constexpr unsigned kUpdateLanes = 64;  // ... and of k_update
 
 // A threshold 2^e (moderate e): every multiple m*t, |m| <= 2*CDSGD_MAX_WORKERS, is exact.
 inline bool is_pow2_threshold(float t)
@@ -380,7 +381,7 @@ int cdsgd_update(float *w_global, float *w_local, const float *grad_local, const
     if (!w_global) return CDSGD_ERR_NULL;
     if (local && (!w_local || !grad_local)) return CDSGD_ERR_NULL;
     if (!local && !global) return CDSGD_ERR_NULL;
-    if (n == 0 || chunks_of(n) > kMaxGrid) return CDSGD_ERR_SIZE;
+    if (n == 0 || units_of(n, kUpdateLanes) > 0xFFFFFFFFull / kUpdateLanes) return CDSGD_ERR_SIZE;
     if (!std::isfinite(lr_local) || !std::isfinite(lr_global)) return CDSGD_ERR_PARAM;
     if (num_workers < 1 || num_workers > CDSGD_MAX_WORKERS) return CDSGD_ERR_WORKERS;
     if (!aligned(w_global, 16) || !aligned(w_local, 16) || !aligned(grad_local, 16) || !aligned(agg, 16))
@@ -391,14 +392,14 @@ int cdsgd_update(float *w_global, float *w_local, const float *grad_local, const
         return CDSGD_ERR_ALIAS;
     const float scale = lr_global / (float)num_workers;
     hipStream_t s = (hipStream_t)hip_stream;
-    const unsigned grid = (unsigned)chunks_of(n);
-    const Extent nn = extent_of(n);
+    const dim3 grid((unsigned)units_of(n, kUpdateLanes)), block(kUpdateLanes);
+    const Extent pieces = extent_of_units(n, kUpdateLanes);
     if (local && global)
-        hipLaunchKernelGGL((k_update<true, true>), dim3(grid), dim3(kBlock), 0, s, w_global, w_local, grad_local, agg, nn, lr_local, scale);
+        hipLaunchKernelGGL((k_update<true, true>), grid, block, 0, s, w_global, w_local, grad_local, agg, pieces, lr_local, scale);
     else if (local)
-        hipLaunchKernelGGL((k_update<true, false>), dim3(grid), dim3(kBlock), 0, s, w_global, w_local, grad_local, agg, nn, lr_local, scale);
+        hipLaunchKernelGGL((k_update<true, false>), grid, block, 0, s, w_global, w_local, grad_local, agg, pieces, lr_local, scale);
     else
-        hipLaunchKernelGGL((k_update<false, true>), dim3(grid), dim3(kBlock), 0, s, w_global, w_local, grad_local, agg, nn, lr_local, scale);
+        hipLaunchKernelGGL((k_update<false, true>), grid, block, 0, s, w_global, w_local, grad_local, agg, pieces, lr_local, scale);
     return launch_status();
 }
 

@@ -155,60 +155,6 @@ __global__ __launch_bounds__(CDSGD_BLOCK) void k_decode_sum(StreamTable tab, int
         decode_sum_chunk<true, POW2>(tab, num_workers, agg, quad0, ext.tail_elems, ext.tail_bytes, t, bias_t);
 }
 
-// a5 + a6 (eq. 10, eq. 11), both from the weight that was loaded.
-template <bool G, bool LOCAL, bool GLOBAL, int GT = kGradF32>
-__device__ __forceinline__ void update_chunk(float *__restrict__ wg, float *__restrict__ wl,
-                                             const void *__restrict__ grad,
-                                             const float *__restrict__ agg, unsigned rem_elems,
-                                             float lr_local, float scale)
-{
-    const unsigned tid = threadIdx.x;
-    f4 w[kQpl], g[kQpl], a[kQpl];
-    int cnt[kQpl];
-#pragma unroll
-    for (unsigned j = 0; j < kQpl; ++j) {
-        const unsigned qi = j * kBlock + tid;
-        cnt[j] = quad_count<G>(rem_elems, qi);
-        w[j] = ld4g<G>(wg, qi, cnt[j]);
-        if (LOCAL) g[j] = ldgrad<G, GT>(grad, qi, cnt[j]);
-        if (GLOBAL) a[j] = ld4g<G>(agg, qi, cnt[j]);
-    }
-#pragma unroll
-    for (unsigned j = 0; j < kQpl; ++j) {
-        const unsigned qi = j * kBlock + tid;
-        if (LOCAL) {
-            f4 v;
-#pragma unroll
-            for (unsigned c = 0; c < 4; ++c) v[c] = __builtin_fmaf(-lr_local, g[j][c], w[j][c]);
-            st4g<G>(wl, qi, cnt[j], v);
-        }
-        if (GLOBAL) {
-            f4 v;
-#pragma unroll
-            for (unsigned c = 0; c < 4; ++c) v[c] = __builtin_fmaf(-scale, a[j][c], w[j][c]);
-            st4g<G>(wg, qi, cnt[j], v);
-        }
-    }
-}
-
-template <bool LOCAL, bool GLOBAL>
-__global__ __launch_bounds__(CDSGD_BLOCK) void k_update(float *__restrict__ wg, float *__restrict__ wl,
-                                                        const float *__restrict__ grad,
-                                                        const float *__restrict__ agg, Extent ext,
-                                                        float lr_local, float scale)
-{
-    const unsigned chunk = blockIdx.x;
-    const size_t quad0 = (size_t)chunk * kChunkQuads;
-    wg += 4 * quad0;
-    if (LOCAL) {
-        wl += 4 * quad0;
-        grad += 4 * quad0;
-    }
-    if (GLOBAL) agg += 4 * quad0;
-    if (chunk < ext.full_chunks) update_chunk<false, LOCAL, GLOBAL>(wg, wl, grad, agg, kChunkElems, lr_local, scale);
-    else update_chunk<true, LOCAL, GLOBAL>(wg, wl, grad, agg, ext.tail_elems, lr_local, scale);
-}
-
 typedef unsigned u4 __attribute__((ext_vector_type(4)));
 
 // values of the codes of a register, as 2-bit two's-complement fields (01 -> +1, 10 -> -1, else 0)
@@ -221,9 +167,55 @@ __device__ __forceinline__ unsigned signed_fields(unsigned w)
 
 
 
+// a5 + a6 (eq. 10, eq. 11) for one tensor, both from the weight that was loaded, in single-wave pieces of
+// 64 quads (`ext` in pieces, as for k_quantize_pack; measured on 2^27 elements: 6.29 TB/s against 6.02 TB/s
+// for 512-lane workgroups with two quads per lane).
+template <bool G, bool LOCAL, bool GLOBAL>
+__device__ __forceinline__ void update_piece(float *__restrict__ wg, float *__restrict__ wl,
+                                             const float *__restrict__ grad, const float *__restrict__ agg,
+                                             unsigned rem_elems, float lr_local, float scale)
+{
+    const unsigned lane = threadIdx.x;
+    const int cnt = quad_count<G>(rem_elems, lane);
+    const f4 w = ld4g<G>(wg, lane, cnt);
+    f4 g = {0.0f, 0.0f, 0.0f, 0.0f}, a = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (LOCAL) g = ld4g<G>(grad, lane, cnt);
+    if (GLOBAL) a = ld4g<G>(agg, lane, cnt);
+    if (LOCAL) {
+        f4 v;
+#pragma unroll
+        for (unsigned c = 0; c < 4; ++c) v[c] = __builtin_fmaf(-lr_local, g[c], w[c]);
+        st4g<G>(wl, lane, cnt, v);
+    }
+    if (GLOBAL) {
+        f4 v;
+#pragma unroll
+        for (unsigned c = 0; c < 4; ++c) v[c] = __builtin_fmaf(-scale, a[c], w[c]);
+        st4g<G>(wg, lane, cnt, v);
+    }
+}
+
+template <bool LOCAL, bool GLOBAL>
+__global__ __launch_bounds__(64) void k_update(float *__restrict__ wg, float *__restrict__ wl,
+                                                     const float *__restrict__ grad, const float *__restrict__ agg,
+                                                     Extent ext, float lr_local, float scale)
+{
+    const unsigned piece = blockIdx.x;
+    const size_t quad0 = (size_t)piece * 64u;
+    wg += 4 * quad0;
+    if (LOCAL) {
+        wl += 4 * quad0;
+        grad += 4 * quad0;
+    }
+    if (GLOBAL) agg += 4 * quad0;
+    if (piece < ext.full_chunks) update_piece<false, LOCAL, GLOBAL>(wg, wl, grad, agg, 256u, lr_local, scale);
+    else update_piece<true, LOCAL, GLOBAL>(wg, wl, grad, agg, ext.tail_elems, lr_local, scale);
+}
+
 // a1-a3 for one tensor, one wave per piece of L = 64 quads (measured: 6.68 TB/s against 6.41 TB/s for
-// 512-lane workgroups with two quads per lane; the other two single-tensor kernels are faster in that
-// shape and keep it).  `ext` describes the tensor in pieces: full_chunks whole pieces, then at most one
+// 512-lane workgroups with two quads per lane; decode-and-sum is faster in that shape and keeps it: in
+// pieces, with the workers' bytes staged through LDS as in the fused pass, it reached 4.1-5.4 TB/s against
+// 5.8 TB/s, a piece of it having too little else to do).  `ext` describes the tensor in pieces: full_chunks whole pieces, then at most one
 // ragged piece of tail_elems elements and tail_bytes packed bytes.
 template <unsigned L>
 __global__ __launch_bounds__(L) void k_quantize_pack(const float *__restrict__ grad, float *__restrict__ resid,

@@ -3,7 +3,7 @@
 
 // Launch shapes and cache policy are chosen by measurement on MI355X; each kernel
 // states its own.  CDSGD_BLOCK x CDSGD_QPL is the shape of the chunk-per-workgroup
-// kernels (k_decode_sum, k_update) and fixes the chunk size of the plan tables.
+// kernel (k_decode_sum) and fixes the chunk size of the plan tables.
 // Non-temporal loads and stores are worth about 15 % (every byte is touched once
 // per step, so nothing should stay in L2 or the memory-side cache).
 #ifndef CDSGD_BLOCK

@@ -175,11 +175,13 @@ def test_workgroup_limit_changes_nothing(P, oracle, full_grads):
         wl.destroy()
 
 
-def test_fused_steps_in_a_hip_graph_replay_like_eager(P):
+@pytest.mark.parametrize("by_ranges", [False, True], ids=["whole_list", "layer_ranges"])
+def test_fused_steps_in_a_hip_graph_replay_like_eager(P, by_ranges):
     """The step is launch-bound on small layer lists, so a caller may capture a run of steps
     in a HIP graph.  The library enqueues kernels only (no memset or copy nodes), so a captured
     period of k steps must replay, several times and with eager work in between, to exactly
-    the state the eager calls reach."""
+    the state the eager calls reach.  by_ranges: the graph holds every step as five launches over
+    ranges of layers, last layers first; the eager side still steps the whole list."""
     pkg, runner, synth = P
     cfg = synth.config("c2_resnet20")
     a = runner.Workload(cfg, dense=True)     # eager
@@ -191,8 +193,13 @@ def test_fused_steps_in_a_hip_graph_replay_like_eager(P):
 
     def run_period(wl):
         for s in period:
-            wl.fused_step(s)
+            if by_ranges and wl is b:
+                for lo, hi in ((60, 65), (41, 60), (40, 41), (7, 40), (0, 7)):
+                    wl.plan.step_range(lo, hi - lo, s, cfg.k, cfg.threshold, cfg.lr, cfg.lr)
+            else:
+                wl.fused_step(s)
 
+    assert cfg.num_tensors == 65
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):            # warm-up on the capture stream, as torch asks
