@@ -8,7 +8,6 @@ constexpr unsigned kBlock = CDSGD_BLOCK;          // lanes per workgroup
 constexpr unsigned kQpl = CDSGD_QPL;              // quads per lane
 constexpr unsigned kChunkQuads = kBlock * kQpl;   // quads (= packed bytes) per chunk
 constexpr unsigned kChunkElems = kChunkQuads * 4; // elements per chunk
-constexpr int kPeerBatch = CDSGD_PEER_BATCH;      // peers whose bytes are in flight together
 static_assert(kQpl == 1 || kQpl == 2 || kQpl == 4, "a lane's packed bytes must fit one register");
 static_assert(CDSGD_GRAD_F32 == 0 && CDSGD_GRAD_BF16 == 1 && CDSGD_GRAD_F16 == 2, "header and kernels agree");
 

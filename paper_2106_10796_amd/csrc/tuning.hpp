@@ -2,8 +2,9 @@
 #pragma once
 
 // Launch shapes and cache policy are chosen by measurement on MI355X; each kernel
-// states its own.  CDSGD_BLOCK x CDSGD_QPL is the shape of the chunk-per-workgroup
-// kernel (k_decode_sum) and fixes the chunk size of the plan tables.
+// states its own.  CDSGD_BLOCK x CDSGD_QPL fixes the chunk size of the plan tables (quads per
+// chunk) and is the shape of the chunk-per-workgroup kernels (k_decode_sum and its sparse form,
+// which are written for 512 x 2 and say so in a static_assert).
 // Non-temporal loads and stores are worth about 15 % (every byte is touched once
 // per step, so nothing should stay in L2 or the memory-side cache).
 #ifndef CDSGD_BLOCK
@@ -21,9 +22,6 @@
 #ifndef CDSGD_NT_STORE
 #define CDSGD_NT_STORE CDSGD_NT
 #endif
-#ifndef CDSGD_NT_CODES
-#define CDSGD_NT_CODES 0
-#endif
 #ifndef CDSGD_XCD_FULL
 #define CDSGD_XCD_FULL 0
 #endif
@@ -38,7 +36,4 @@
 #endif
 #ifndef CDSGD_FULL_BLOCK
 #define CDSGD_FULL_BLOCK 64
-#endif
-#ifndef CDSGD_PEER_BATCH
-#define CDSGD_PEER_BATCH 4
 #endif
