@@ -33,10 +33,10 @@ def build() -> str:
 
 
 def ensure_built() -> str:
-    """Build if the client is missing or older than its source or than either library."""
-    deps = [SRC, os.path.join(ROOT, "paper_2106_10796_amd", "libcdsgd.so"), os.path.join(ROOT, "oracle", "liboracle_cdsgd.so"),
-            os.path.join(ROOT, "include", "cdsgd.h")]
-    if os.path.exists(EXE) and all(os.path.exists(d) and os.path.getmtime(EXE) >= os.path.getmtime(d) for d in deps):
+    """Build if the client is missing or older than its source or the header it is compiled against.
+    (It links the two libraries dynamically, so a rebuilt library needs no rebuilt client.)"""
+    deps = [SRC, os.path.join(ROOT, "include", "cdsgd.h")]
+    if os.path.exists(EXE) and all(os.path.getmtime(EXE) >= os.path.getmtime(d) for d in deps):
         return EXE
     return build()
 

@@ -1,6 +1,7 @@
 """The C ABI used from a plain C++ program (no Python, no torch: hipMalloc'd buffers, Alg. 1 through
 cdsgd_trainer_*, the formal phase also layer by layer on a stream of its own), checked by that program
-bit for bit against the oracle.  The program is tests/native/abi_client.cpp."""
+bit for bit against the oracle.  The program is tests/native/abi_client.cpp.  (The file's name puts it
+near the end of the collection order: it starts a second process on the GPU.)"""
 import importlib.util
 import os
 import subprocess
