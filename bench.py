@@ -267,6 +267,20 @@ def layer_by_layer(name, steps, min_seconds=0.3):
         fn()
         b = timed_blocks(lambda: [fn() for _ in range(steps)], steps, stream, min_seconds=min_seconds, min_blocks=5)
         out["ms_" + tag] = b["median_ms_per_step"]
+    # the per-tensor launches again, replayed from a HIP graph (the launches cost the host nothing then)
+    side = torch.cuda.Stream()
+    side.wait_stream(stream)
+    with torch.cuda.stream(side):
+        forms["one_range_per_tensor"]()
+    stream.wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        forms["one_range_per_tensor"]()
+    graph.replay()
+    b = timed_blocks(lambda: [graph.replay() for _ in range(steps)], steps, stream, min_seconds=min_seconds, min_blocks=5)
+    out["ms_one_range_per_tensor_hip_graph"] = b["median_ms_per_step"]
+    del graph
     wl.destroy()
     return out
 
