@@ -171,10 +171,20 @@ def stream_ceilings(wl, min_seconds=0.3):
                       "probe_3r_3w": ([a, b, g], [c, d, e])})
     for name, (rd, wr) in probe.items():
         ops[name] = ((lambda rd=rd, wr=wr: binding.cdsgd_probe_streams(rd, wr, sink)), 4.0 * n * (len(rd) + len(wr)))
+    if fp32_grad:
+        # the same mixes with the resident waves per compute unit bounded (LDS asked for and not used), the
+        # knob the library's single-wave kernels are launched with: 20, 13 and 10 waves instead of 32
+        for lds, waves in ((8192, 20), (12288, 13), (16384, 10)):
+            for tag in ("probe_3r_2w", "probe_3r_3w"):
+                rd, wr = probe[tag]
+                ops["%s_%dwaves" % (tag, waves)] = (
+                    (lambda rd=rd, wr=wr, lds=lds: binding.cdsgd_probe_streams(rd, wr, sink, lds_bytes=lds)),
+                    4.0 * n * (len(rd) + len(wr)))
     out = {"elements": n,
            "note": "GB/s of bare streaming on the workload's own fp32 arenas, >= %.1f s each, after the headline (warm "
                    "GPU): probe_<R>r_<W>w = the library's streaming probe with R read and W write streams "
-                   "(cdsgd_probe_streams), the others torch's elementwise kernels" % min_seconds}
+                   "(cdsgd_probe_streams), _<K>waves = at most K waves resident per compute unit; the others torch's "
+                   "elementwise kernels" % min_seconds}
     for name, (fn, nbytes) in ops.items():
         for _ in range(3):
             fn()
@@ -574,6 +584,9 @@ def main():
     ap.add_argument("--only-layer-by-layer", action="store_true",
                     help="time only the compressed pass enqueued layer by layer (cdsgd_step_fused_range) against the "
                          "one-launch pass and print those figures instead of the benchmark line")
+    ap.add_argument("--only-stream-ceilings", action="store_true",
+                    help="time the headline workload and the bare streaming kernels on its arenas, nothing else (for "
+                         "collecting the same counters on k_fused_compressed and on k_probe_streams in one profiler run)")
     ap.add_argument("--only-overlap", action="store_true",
                     help="run only the overlap demo (split step on two streams beside a forward stand-in) and print "
                          "its figures instead of the benchmark line")
@@ -612,6 +625,14 @@ def main():
         r = time_correction_sum(args.workload, args.steps, args.warmup, min_seconds=min(0.5, args.min_seconds))
         r["workload"] = args.workload
         print(json.dumps(r))
+        return 0
+    if args.only_stream_ceilings:
+        head, wl = time_workload(args.workload, args.steps, args.warmup, want_correction=False,
+                                 min_seconds=args.min_seconds)
+        out = {"headline": {k: head[k] for k in ("workload", "ms_per_step", "gbs", "frac_hbm_peak")},
+               "stream_ceilings": stream_ceilings(wl, min_seconds=min(0.3, args.min_seconds))}
+        wl.destroy()
+        print(json.dumps(out))
         return 0
     head, wl = time_workload(args.workload, args.steps, args.warmup, want_correction=True,
                              want_unfused=not args.no_extra, min_seconds=args.min_seconds)

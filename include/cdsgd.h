@@ -346,9 +346,13 @@ int cdsgd_trainer_destroy(cdsgd_trainer *trainer);
  *   n               a multiple of 256
  *   sink            device buffer of n / 256 floats, needed (and practically never written) when
  *                   num_writes == 0; may be NULL otherwise
+ *   lds_bytes       LDS that every one-wave workgroup asks for and never touches (0 .. 65536, else
+ *                   CDSGD_ERR_PARAM): it bounds the waves resident per compute unit at
+ *                   163840 / lds_bytes, the knob the library's own single-wave kernels are launched
+ *                   with; 0 = no bound (32 waves)
  */
 int cdsgd_probe_streams(const float *const *reads, int num_reads, float *const *writes, int num_writes,
-                        size_t n, float *sink, void *hip_stream);
+                        size_t n, float *sink, unsigned lds_bytes, void *hip_stream);
 
 /*
  * cdsgd_step_fused for callers that cannot allocate device memory: code under HIP graph

@@ -95,7 +95,7 @@ def lib():
         L.cdsgd_plan_set_peer_format.restype = i
         L.cdsgd_plan_set_peer_format.argtypes = [vp, i]
         L.cdsgd_probe_streams.restype = i
-        L.cdsgd_probe_streams.argtypes = [ctypes.POINTER(vp), i, ctypes.POINTER(vp), i, sz, vp, vp]
+        L.cdsgd_probe_streams.argtypes = [ctypes.POINTER(vp), i, ctypes.POINTER(vp), i, sz, vp, ctypes.c_uint, vp]
         L.cdsgd_plan_set_max_workgroups.restype = i
         L.cdsgd_plan_set_max_workgroups.argtypes = [vp, i]
         L.cdsgd_step_local.restype = i
@@ -214,13 +214,13 @@ def cdsgd_decode_sum_sparse(sparse_list, agg, threshold):
     _check(st, "cdsgd_decode_sum_sparse")
 
 
-def cdsgd_probe_streams(reads, writes, sink=None):
+def cdsgd_probe_streams(reads, writes, sink=None, lds_bytes=0):
     """Bare streaming of len(reads) read and len(writes) write streams (cdsgd_probe_streams)."""
     n = (reads + writes)[0].numel()
     ra = (ctypes.c_void_p * max(len(reads), 1))(*[_dev(t, torch.float32, n, "reads").value for t in reads])
     wa = (ctypes.c_void_p * max(len(writes), 1))(*[_dev(t, torch.float32, n, "writes").value for t in writes])
     st = lib().cdsgd_probe_streams(ra, len(reads), wa, len(writes), n,
-                                   _dev(sink, torch.float32, None, "sink"), _stream())
+                                   _dev(sink, torch.float32, None, "sink"), int(lds_bytes), _stream())
     _check(st, "cdsgd_probe_streams")
 
 

@@ -60,6 +60,19 @@ namespace {
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
+// LDS that the single-wave kernels ask for at launch and never touch: it bounds the waves resident per
+// compute unit (160 KiB / bytes).  With all 32 resident, more requests queue in front of HBM than it takes
+// to keep it busy, and a mix of reads and writes is then served more slowly.  Measured (2^27 elements or the
+// VGG-16-shaped list; TB/s at 32 / 26 / 22 / 20 / 17 / 16 / 13 / 10 resident waves):
+//   correction pass with agg_full   6.42-6.45 / 6.40 / 6.51 / 6.66-6.67 / 6.55 / 6.55-6.60 / 6.41 / 5.88
+//   quantise-and-pack               6.71 / 6.72 / - / 6.83 / - / 6.88 / 6.09 / 5.10
+//   update, both rules              6.36 / 6.34 / - / 6.55 / - / 6.50 / 6.55 / 6.18
+//   correction pass, sum in kernel  6.19 / 6.39-6.41 / 6.35 / 6.24 / - / 5.97
+// eq. 11 alone and the compressed pass (whose workgroups already hold 4-16 KiB of staged codes) lose with
+// any bound and get none.
+constexpr unsigned kLdsFor20Waves = 8192;
+constexpr unsigned kLdsFor26Waves = 6144;
+
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 // Do [a, a + na) and [b, b + nb) share a byte?  (NULL never overlaps.)
@@ -272,7 +285,8 @@ int launch_full_pass(const PlanTables *plan, int local_mode, float lr_local, flo
     const dim3 grid(plan->grid_size(num_pieces, kFullBlock)), block(kFullBlock);
     const int np = plan->num_workers - 1;
 #define CDSGD_LAUNCH_FULL_T(SUM, LOCAL, GT)                                                                    \
-    hipLaunchKernelGGL((k_fused_full<SUM, LOCAL, GT>), grid, block, 0, s, plan->tensors, plan->chunk_table(),    \
+    hipLaunchKernelGGL((k_fused_full<SUM, LOCAL, GT>), grid, block, (SUM ? kLdsFor26Waves : kLdsFor20Waves), s,  \
+                       plan->tensors, plan->chunk_table(),                                                      \
                        num_pieces, plan->peer_grads, np, plan->self, lr_local, scale)
 #define CDSGD_LAUNCH_FULL(SUM, LOCAL)                                                                          \
     do {                                                                                                       \
@@ -339,7 +353,7 @@ int cdsgd_quantize_pack(const float *grad, float *residual, uint32_t *packed, si
         overlap2(packed, (size_t)packed_bytes_of(n), grad, n * sizeof(float)) ||
         overlap2(packed, (size_t)packed_bytes_of(n), residual, n * sizeof(float)))
         return CDSGD_ERR_ALIAS;
-    hipLaunchKernelGGL(k_quantize_pack<kQuantLanes>, dim3((unsigned)units_of(n, kQuantLanes)), dim3(kQuantLanes), 0,
+    hipLaunchKernelGGL(k_quantize_pack<kQuantLanes>, dim3((unsigned)units_of(n, kQuantLanes)), dim3(kQuantLanes), kLdsFor20Waves,
                        (hipStream_t)hip_stream, grad, residual, reinterpret_cast<uint8_t *>(packed),
                        extent_of_units(n, kQuantLanes), threshold);
     return launch_status();
@@ -395,7 +409,7 @@ int cdsgd_update(float *w_global, float *w_local, const float *grad_local, const
     const dim3 grid((unsigned)units_of(n, kUpdateLanes)), block(kUpdateLanes);
     const Extent pieces = extent_of_units(n, kUpdateLanes);
     if (local && global)
-        hipLaunchKernelGGL((k_update<true, true>), grid, block, 0, s, w_global, w_local, grad_local, agg, pieces, lr_local, scale);
+        hipLaunchKernelGGL((k_update<true, true>), grid, block, kLdsFor20Waves, s, w_global, w_local, grad_local, agg, pieces, lr_local, scale);
     else if (local)
         hipLaunchKernelGGL((k_update<true, false>), grid, block, 0, s, w_global, w_local, grad_local, agg, pieces, lr_local, scale);
     else
@@ -738,10 +752,10 @@ int cdsgd_plan_set_peer_format(cdsgd_plan *plan, int format)
 }
 
 int cdsgd_probe_streams(const float *const *reads, int num_reads, float *const *writes, int num_writes, size_t n,
-                        float *sink, void *hip_stream)
+                        float *sink, unsigned lds_bytes, void *hip_stream)
 {
     if (num_reads < 0 || num_reads > kProbeMaxReads || num_writes < 0 || num_writes > kProbeMaxWrites ||
-        num_reads + num_writes == 0)
+        num_reads + num_writes == 0 || lds_bytes > 65536u)
         return CDSGD_ERR_PARAM;
     if ((num_reads > 0 && !reads) || (num_writes > 0 && !writes) || (num_writes == 0 && !sink)) return CDSGD_ERR_NULL;
     if (n == 0 || n % 256 != 0 || n / 256 > 0xFFFFFFFFull / 64) return CDSGD_ERR_SIZE;
@@ -764,7 +778,7 @@ int cdsgd_probe_streams(const float *const *reads, int num_reads, float *const *
     }
     const dim3 grid((unsigned)(n / 256)), block(64);
     hipStream_t s = (hipStream_t)hip_stream;
-#define CDSGD_PROBE(R, W) hipLaunchKernelGGL((k_probe_streams<R, W>), grid, block, 0, s, p, sink)
+#define CDSGD_PROBE(R, W) hipLaunchKernelGGL((k_probe_streams<R, W>), grid, block, lds_bytes, s, p, sink)
     switch ((num_reads > 3 ? 4 : num_reads) * 4 + num_writes) {
     case 4 * 4 + 0: CDSGD_PROBE(-1, 0); break;
     case 4 * 4 + 1: CDSGD_PROBE(-1, 1); break;

@@ -75,10 +75,10 @@ int main()
     {
         const float *rd[3] = {A, A + 4096, A + 8192};
         float *wr[3] = {A + 12288, A + 16384, A + 12288 + 4};
-        bad += cdsgd_probe_streams(rd, 18, wr, 1, 1024, A, nullptr) != CDSGD_ERR_PARAM;
-        bad += cdsgd_probe_streams(rd, 3, wr, 0, 1024, nullptr, nullptr) != CDSGD_ERR_NULL;
-        bad += cdsgd_probe_streams(rd, 3, wr, 2, 1000, nullptr, nullptr) != CDSGD_ERR_SIZE;
-        bad += cdsgd_probe_streams(rd, 3, wr, 3, 1024, nullptr, nullptr) != CDSGD_ERR_ALIAS;
+        bad += cdsgd_probe_streams(rd, 18, wr, 1, 1024, A, 0, nullptr) != CDSGD_ERR_PARAM;
+        bad += cdsgd_probe_streams(rd, 3, wr, 0, 1024, nullptr, 0, nullptr) != CDSGD_ERR_NULL;
+        bad += cdsgd_probe_streams(rd, 3, wr, 2, 1000, nullptr, 0, nullptr) != CDSGD_ERR_SIZE;
+        bad += cdsgd_probe_streams(rd, 3, wr, 3, 1024, nullptr, 8192, nullptr) != CDSGD_ERR_ALIAS;
     }
     bad += cdsgd_plan_set_thresholds(nullptr, nullptr) != CDSGD_ERR_NULL;
     bad += cdsgd_build_id() == nullptr;

@@ -114,17 +114,18 @@ def test_probe_streams_argument_errors(L):
     r = (ctypes.c_void_p * 3)(A, A + 0x100000, A + 0x200000)
     w = (ctypes.c_void_p * 3)(A + 0x300000, A + 0x400000, A + 0x500000)
     S = A + 0x600000
-    assert f(r, 18, w, 1, 1024, S, None) == ERR_PARAM
-    assert f(r, 1, w, 4, 1024, S, None) == ERR_PARAM
-    assert f(r, 0, w, 0, 1024, S, None) == ERR_PARAM
-    assert f(None, 1, w, 1, 1024, S, None) == ERR_NULL
-    assert f(r, 2, w, 0, 1024, None, None) == ERR_NULL            # read-only needs the sink
-    assert f(r, 1, w, 1, 1000, S, None) == ERR_SIZE              # not a multiple of 256
-    assert f(r, 1, w, 1, 0, S, None) == ERR_SIZE
+    assert f(r, 18, w, 1, 1024, S, 0, None) == ERR_PARAM
+    assert f(r, 1, w, 4, 1024, S, 0, None) == ERR_PARAM
+    assert f(r, 1, w, 1, 1024, S, 65537, None) == ERR_PARAM
+    assert f(r, 0, w, 0, 1024, S, 0, None) == ERR_PARAM
+    assert f(None, 1, w, 1, 1024, S, 0, None) == ERR_NULL
+    assert f(r, 2, w, 0, 1024, None, 0, None) == ERR_NULL            # read-only needs the sink
+    assert f(r, 1, w, 1, 1000, S, 0, None) == ERR_SIZE              # not a multiple of 256
+    assert f(r, 1, w, 1, 0, S, 0, None) == ERR_SIZE
     odd = (ctypes.c_void_p * 1)(A + 4)
-    assert f(odd, 1, w, 1, 1024, S, None) == ERR_ALIGN
-    assert f(r, 1, r, 1, 1024, S, None) == ERR_ALIAS             # writing what is read
-    assert f(r, 1, (ctypes.c_void_p * 2)(A + 0x300000, A + 0x300010), 2, 1024, S, None) == ERR_ALIAS
+    assert f(odd, 1, w, 1, 1024, S, 0, None) == ERR_ALIGN
+    assert f(r, 1, r, 1, 1024, S, 0, None) == ERR_ALIAS             # writing what is read
+    assert f(r, 1, (ctypes.c_void_p * 2)(A + 0x300000, A + 0x300010), 2, 1024, S, 0, None) == ERR_ALIAS
 
 
 def test_status_strings(L):

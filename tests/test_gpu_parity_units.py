@@ -148,7 +148,7 @@ def test_probe_streams_moves_what_it_says(B):
                 continue
             fulls = [guarded(n, torch.float32, 4.0) for _ in range(W)]
             sink = torch.full((n // 256,), 7.0, device="cuda")
-            B.cdsgd_probe_streams(reads[:R], [v for _, v in fulls], sink)
+            B.cdsgd_probe_streams(reads[:R], [v for _, v in fulls], sink, lds_bytes=(0, 8192, 16384)[(R + W) % 3])
             torch.cuda.synchronize()
             want = np.zeros(n, np.float32)
             for i in range(R):
