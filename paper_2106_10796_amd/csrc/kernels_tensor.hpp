@@ -9,17 +9,23 @@ namespace {
 // A lane keeps the packed bytes of its kQpl quads of one worker in one
 // register: byte j = quad j.
 
-// Literal fp32 chain: agg += value(code) for the 4*kQpl elements of this lane,
-// one rounded add per element.  The codes are first rewritten, 16 at a time,
-// as 2-bit two's-complement counts (01 -> +1, 10 -> -1, 00 and 11 -> 0) so
-// that one signed bit-field extract yields the multiplier.
-__device__ __forceinline__ void chain_codes(f4 (&agg)[kQpl], unsigned w, float t)
+typedef unsigned u4 __attribute__((ext_vector_type(4)));
+
+// values of the codes of a register, as 2-bit two's-complement fields (01 -> +1, 10 -> -1, else 0)
+__device__ __forceinline__ unsigned signed_fields(unsigned w)
 {
     const unsigned x = w & 0x55555555u;
     const unsigned y = (w >> 1) & 0x55555555u;
-    const unsigned lo = x ^ y;
-    const unsigned hi = y & ~x;
-    const unsigned s = lo | (hi << 1);
+    return (x ^ y) | ((y & ~x) << 1);
+}
+
+// Literal fp32 chain: agg += value(code) for the 4*kQpl elements of this lane,
+// one rounded add per element.  The codes are first rewritten, 16 at a time,
+// as 2-bit two's-complement fields so that one signed bit-field extract
+// yields the multiplier.
+__device__ __forceinline__ void chain_codes(f4 (&agg)[kQpl], unsigned w, float t)
+{
+    const unsigned s = signed_fields(w);
 #pragma unroll
     for (unsigned j = 0; j < kQpl; ++j) {
 #pragma unroll
@@ -58,22 +64,10 @@ __device__ __forceinline__ void counts_to_sum(f4 (&agg)[kQpl], const unsigned (&
     }
 }
 
-// a4 for one tensor; the worker pointers travel in the kernel arguments.
+// The workers' stream pointers of a single-tensor call; they travel in the kernel arguments.
 struct StreamTable {
     const uint8_t *p[CDSGD_MAX_WORKERS];
 };
-
-typedef unsigned u4 __attribute__((ext_vector_type(4)));
-
-// values of the codes of a register, as 2-bit two's-complement fields (01 -> +1, 10 -> -1, else 0)
-__device__ __forceinline__ unsigned signed_fields(unsigned w)
-{
-    const unsigned x = w & 0x55555555u;
-    const unsigned y = (w >> 1) & 0x55555555u;
-    return (x ^ y) | ((y & ~x) << 1);
-}
-
-
 
 // a4 for one tensor: 512 lanes per chunk, the workers' bytes staged through LDS.  Sixteen workers at
 // a time, wave w fetches the chunk's 1 KiB of workers w and w + 8 of the batch with one 128-bit load per
@@ -82,9 +76,8 @@ __device__ __forceinline__ unsigned signed_fields(unsigned w)
 // worker back (measured on 2^27 elements, N = 16, count form: 6.17 TB/s, against 5.6-5.8 TB/s with a
 // byte-wide global load per worker and lane, four workers in flight at a time).
 template <bool POW2>
-__global__ __launch_bounds__(512) void k_decode_sum(StreamTable tab, int num_workers,
-                                                           float *__restrict__ agg_out, Extent ext, float t,
-                                                           float bias_t)
+__global__ __launch_bounds__(512) void k_decode_sum(StreamTable tab, int num_workers, float *__restrict__ agg_out,
+                                                    Extent ext, float t, float bias_t)
 {
     __shared__ __attribute__((aligned(16))) uint8_t rows[16][kChunkQuads];
     static_assert(kChunkQuads == 1024 && kBlock == 512 && kQpl == 2, "one 128-bit load per lane covers a worker's chunk");
