@@ -70,73 +70,59 @@ __global__ __launch_bounds__(256) void k_sparse_encode(const uint32_t *__restric
     if (i == 0 && seg_words) seg_words[blockIdx.x] = 8u + total;
 }
 
-// a4 on sparse streams, one tensor: 512 lanes per chunk, lane tid takes quads tid and 512 + tid.
-// Four workers at a time are rebuilt into LDS (lane i < 256 rebuilds packed word i of each), then
-// every lane picks its two bytes of each.
+// a4 on sparse streams, one tensor: 512 lanes per chunk, lane tid takes quads tid and 512 + tid, the
+// workers' bytes staged through LDS sixteen workers at a time as in k_decode_sum.  Per batch the 16 x 8
+// bitmap words go to LDS first (one word per lane); then wave w rebuilds the chunk's 256 packed words of
+// workers w and w + 8, four consecutive words per lane with one 128-bit load of the non-zero ones among
+// them; then every lane picks its two bytes of each worker.
 template <bool POW2>
 __global__ __launch_bounds__(512) void k_decode_sum_sparse(StreamTable tab, int num_workers,
                                                            float *__restrict__ agg_out, Extent ext, float t,
                                                            float bias_t)
 {
-    __shared__ uint32_t words[4][kSegWords];
-    const unsigned tid = threadIdx.x;
+    __shared__ __attribute__((aligned(16))) uint8_t rows[16][kChunkQuads];
+    __shared__ uint32_t bitmaps[16][8];
+    static_assert(kChunkQuads == 1024 && kBlock == 512 && kQpl == 2, "four packed words per lane cover a worker's chunk");
+    const unsigned tid = threadIdx.x, lane = tid & 63u;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(tid >> 6));
     const unsigned chunk = blockIdx.x;
     const bool tail = chunk >= ext.full_chunks;
     const unsigned rem_elems = tail ? ext.tail_elems : kChunkElems;
-    f4 agg[2] = {f4{0.0f, 0.0f, 0.0f, 0.0f}, f4{0.0f, 0.0f, 0.0f, 0.0f}};
+    f4 agg[kQpl] = {f4{0.0f, 0.0f, 0.0f, 0.0f}, f4{0.0f, 0.0f, 0.0f, 0.0f}};
     unsigned acc[4] = {0u, 0u, 0u, 0u};
-    for (int p0 = 0; p0 < num_workers; p0 += 4) {
-        const int np = num_workers - p0 < 4 ? num_workers - p0 : 4;
-        if (tid < kSegWords) {
-            for (int k = 0; k < np; ++k) {
+    for (int p0 = 0; p0 < num_workers; p0 += 16) {
+        const int np = num_workers - p0 < 16 ? num_workers - p0 : 16;
+        if (tid < 128u) {
+            const unsigned k = tid >> 3;
+            if ((int)k < np)
+                bitmaps[k][tid & 7u] =
+                    (reinterpret_cast<const uint32_t *>(tab.p[p0 + (int)k]) + (size_t)chunk * kSegStride)[tid & 7u];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int k = wave + 8 * h;
+            if (k < np) {
                 const uint32_t *seg = reinterpret_cast<const uint32_t *>(tab.p[p0 + k]) + (size_t)chunk * kSegStride;
-                const unsigned m = tid >> 5, bit = tid & 31u;
-                const unsigned bm = seg[m];
-                uint32_t v = 0u;
-                if ((bm >> bit) & 1u) {
-                    unsigned before = 0;
-                    for (unsigned x = 0; x < m; ++x) before += (unsigned)__builtin_popcount(seg[x]);
-                    v = seg[8u + before + (unsigned)__builtin_popcount(bm & ((1u << bit) - 1u))];
-                }
-                words[k][tid] = v;
+                // (pad words past the end of the stream have no bit set: a ragged chunk needs no other care)
+                *reinterpret_cast<u4 *>(&rows[k][16u * lane]) = sparse_words4(seg, bitmaps[k], 4u * lane);
             }
         }
         __syncthreads();
         for (int k = 0; k < np; ++k) {
-            const uint8_t *bytes = reinterpret_cast<const uint8_t *>(words[k]);
-            const unsigned w = (unsigned)bytes[tid] | ((unsigned)bytes[512u + tid] << 8);
-            if (POW2) {
-                const unsigned z = ((w & 0x55555555u) | 0xAAAAAAAAu) - ((w >> 1) & 0x55555555u);
-                acc[0] += z & 0x03030303u;
-                acc[1] += (z >> 2) & 0x03030303u;
-                acc[2] += (z >> 4) & 0x03030303u;
-                acc[3] += (z >> 6) & 0x03030303u;
-            } else {
-                const unsigned sf = signed_fields(w);
-#pragma unroll
-                for (unsigned j = 0; j < 2; ++j)
-#pragma unroll
-                    for (unsigned c = 0; c < 4; ++c) {
-                        const int mlt = ((int)(sf << (30u - (8u * j + 2u * c)))) >> 30;
-                        agg[j][c] = __builtin_fmaf((float)mlt, t, agg[j][c]);
-                    }
-            }
+            const unsigned w = (unsigned)rows[k][tid] | ((unsigned)rows[k][512u + tid] << 8);
+            if (POW2) count_codes(acc, w);
+            else chain_codes(agg, w, t);
         }
         __syncthreads();
     }
+    if (POW2) counts_to_sum(agg, acc, t, bias_t);
     float *out = agg_out + (size_t)chunk * kChunkElems;
 #pragma unroll
-    for (unsigned j = 0; j < 2; ++j) {
-        const unsigned qi = j * 512u + tid;
-        if (POW2) {
-#pragma unroll
-            for (unsigned c = 0; c < 4; ++c)
-                agg[j][c] = __builtin_fmaf((float)((acc[c] >> (8u * j)) & 0xFFu), t, bias_t);
-        }
-        int cnt = (int)rem_elems - (int)(4u * qi);
-        cnt = cnt < 0 ? 0 : (cnt > 4 ? 4 : cnt);
-        if (cnt == 4) st4(out, qi, agg[j]);
-        else st4g<true>(out, qi, cnt, agg[j]);
+    for (unsigned j = 0; j < kQpl; ++j) {
+        const unsigned qi = j * kBlock + tid;
+        if (!tail) st4(out, qi, agg[j]);
+        else st4g<true>(out, qi, quad_count<true>(rem_elems, qi), agg[j]);
     }
 }
 
