@@ -293,6 +293,24 @@ def cdsgd_step_fused_static(tensors, peers, num_workers, self_rank, step, k, thr
     _check(st, "cdsgd_step_fused_static")
 
 
+class StaticLayerList:
+    """A layer list marshalled once for cdsgd_step_fused_static: the host arrays the call reads are built
+    here, so that step() costs what the C entry point costs (the tensors are kept alive by this object)."""
+
+    def __init__(self, tensors, peers, num_workers, grad_dtype=torch.float32):
+        self._keep = (tensors, peers)
+        self._n = len(tensors)
+        self._num_workers = int(num_workers)
+        self._grad = GRAD_DTYPES[grad_dtype]
+        self._arr, self._rows, self._rows_keep = _marshal_layer_list(tensors, peers, num_workers, grad_dtype)
+
+    def step(self, self_rank, step, k, threshold, lr_local, lr_global):
+        st = lib().cdsgd_step_fused_static(self._arr, self._n, self._rows, self._num_workers, int(self_rank),
+                                           self._grad, int(step), int(k), float(threshold), float(lr_local),
+                                           float(lr_global), _stream())
+        _check(st, "cdsgd_step_fused_static")
+
+
 class Plan:
     """A fused-step plan over a layer list (cdsgd_plan_create / cdsgd_step_fused / cdsgd_plan_destroy).
 

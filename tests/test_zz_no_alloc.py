@@ -83,9 +83,13 @@ def _assert_same(copies, tag):
 def _run_pair(B, rng, sizes, N, self_rank, t, steps, k, grad_dtype=torch.float32, lr_l=0.4, lr_g=0.1):
     copies, peers = _make_case(B, rng, sizes, N, self_rank, t, grad_dtype)
     plan = B.Plan(copies[0][1], peers, N, self_rank, grad_dtype=grad_dtype)
-    for s in steps:
+    marshalled = B.StaticLayerList(copies[1][1], peers, N, grad_dtype=grad_dtype)   # the same call, arrays built once
+    for turn, s in enumerate(steps):
         plan.step(s, k, t, lr_l, lr_g)
-        B.cdsgd_step_fused_static(copies[1][1], peers, N, self_rank, s, k, t, lr_l, lr_g, grad_dtype=grad_dtype)
+        if turn % 2:
+            marshalled.step(self_rank, s, k, t, lr_l, lr_g)
+        else:
+            B.cdsgd_step_fused_static(copies[1][1], peers, N, self_rank, s, k, t, lr_l, lr_g, grad_dtype=grad_dtype)
         torch.cuda.synchronize()
         _assert_same(copies, "sizes=%s N=%d self=%d t=%g step %d" % (sizes[:4], N, self_rank, t, s))
     # something was actually computed: weights moved, codes were written on compressed steps
