@@ -525,15 +525,23 @@ int launch_formal_pass(const PlanTables *plan, long step, int k, float threshold
     hipStream_t s = (hipStream_t)hip_stream;
     const int num_peers = plan->num_workers - 1;
     const unsigned waves = num_peers <= kFewPeers ? 1u : kPieceWavesMany;
+    const bool many = num_peers > 16;  // count form: the kernel compiled for more waves per SIMD
     const unsigned long long num_pieces = (unsigned long long)plan->num_chunks * (kChunkQuads / (64u * waves));
     const dim3 grid(plan->grid_size(num_pieces, 64u * waves)), block(64u * waves);
 #define CDSGD_LAUNCH_COMPRESSED_S(W, POW2, LOCAL, GT, SPARSE)                                                  \
     hipLaunchKernelGGL((k_fused_compressed<W, POW2, LOCAL, GT, SPARSE>), grid, block, 0, s, plan->tensors,      \
                        plan->chunk_table(), num_pieces, plan->peers, num_peers, plan->self, threshold, lr_local, \
                        scale)
+#define CDSGD_LAUNCH_COMPRESSED_M(LOCAL, GT, SPARSE)                                                           \
+    hipLaunchKernelGGL((k_fused_compressed_many<LOCAL, GT, SPARSE>), grid, block, 0, s, plan->tensors,          \
+                       plan->chunk_table(), num_pieces, plan->peers, num_peers, plan->self, threshold, lr_local, \
+                       scale)
 #define CDSGD_LAUNCH_COMPRESSED_W(W, POW2, LOCAL, GT)                                                          \
     do {                                                                                                       \
-        if (plan->peers_sparse) CDSGD_LAUNCH_COMPRESSED_S(W, POW2, LOCAL, GT, true);                            \
+        if (POW2 && many) {                                                                                    \
+            if (plan->peers_sparse) CDSGD_LAUNCH_COMPRESSED_M(LOCAL, GT, true);                                 \
+            else CDSGD_LAUNCH_COMPRESSED_M(LOCAL, GT, false);                                                   \
+        } else if (plan->peers_sparse) CDSGD_LAUNCH_COMPRESSED_S(W, POW2, LOCAL, GT, true);                     \
         else CDSGD_LAUNCH_COMPRESSED_S(W, POW2, LOCAL, GT, false);                                              \
     } while (0)
 #define CDSGD_LAUNCH_COMPRESSED_T(POW2, LOCAL, GT)                                                            \
@@ -559,6 +567,7 @@ int launch_formal_pass(const PlanTables *plan, long step, int k, float threshold
 #undef CDSGD_LAUNCH_COMPRESSED
 #undef CDSGD_LAUNCH_COMPRESSED_T
 #undef CDSGD_LAUNCH_COMPRESSED_W
+#undef CDSGD_LAUNCH_COMPRESSED_M
 #undef CDSGD_LAUNCH_COMPRESSED_S
     return launch_status();
 }

@@ -193,18 +193,12 @@ __device__ __forceinline__ void fused_piece(const TensorDesc &d, const uint8_t *
     }
 }
 
+// The compressed pass over the pieces a workgroup takes (the body of the two kernels below).
 template <unsigned kPieceWaves, bool POW2, bool WRITE_LOCAL, int GT, bool SPARSE>
-// Waves per SIMD: the count form is left to what its registers allow (5 for packed peers, 6 for sparse
-// ones: forcing 4, 6, 7 or 8 on the packed form is 0-4 % slower, forcing 5 on the sparse one 6 %); the
-// literal chain has three times the arithmetic per worker and runs 3 % faster with the registers squeezed
-// for 6 (4 GiB bucket: 4.70 against 4.84 ms).
-__attribute__((amdgpu_waves_per_eu(POW2 ? 1 : 6, POW2 ? 8 : 6)))
-__global__ __launch_bounds__(64 * kPieceWaves) void k_fused_compressed(const TensorDesc *__restrict__ tensors,
-                                                                       const ChunkRef *__restrict__ chunks,
-                                                                       unsigned long long num_pieces,
-                                                                       const uint8_t *const *__restrict__ peers,
-                                                                       int num_peers, int self, float t_call,
-                                                                       float lr_local, float scale)
+__device__ __forceinline__ void compressed_pass(const TensorDesc *__restrict__ tensors,
+                                                const ChunkRef *__restrict__ chunks, unsigned long long num_pieces,
+                                                const uint8_t *const *__restrict__ peers, int num_peers, int self,
+                                                float t_call, float lr_local, float scale)
 {
     constexpr unsigned kPieceQuads = 64 * kPieceWaves;
     constexpr unsigned kPerChunk = kChunkQuads / kPieceQuads;
@@ -227,6 +221,39 @@ __global__ __launch_bounds__(64 * kPieceWaves) void k_fused_compressed(const Ten
                                                                   scale, lds);
         }
     }
+}
+
+// Waves per SIMD.  With up to 16 peers the count form is left to what its registers allow (5 for packed
+// peers, 6 for sparse ones: forcing 4, 6, 7 or 8 on the packed form is 0-4 % slower, forcing 5 on the
+// sparse one 6 %); the literal chain has three times the arithmetic per worker and runs 3 % faster with
+// the registers squeezed for 6 (4 GiB bucket: 4.70 against 4.84 ms).
+template <unsigned kPieceWaves, bool POW2, bool WRITE_LOCAL, int GT, bool SPARSE>
+__attribute__((amdgpu_waves_per_eu(POW2 ? 1 : 6, POW2 ? 8 : 6)))
+__global__ __launch_bounds__(64 * kPieceWaves) void k_fused_compressed(const TensorDesc *__restrict__ tensors,
+                                                                       const ChunkRef *__restrict__ chunks,
+                                                                       unsigned long long num_pieces,
+                                                                       const uint8_t *const *__restrict__ peers,
+                                                                       int num_peers, int self, float t_call,
+                                                                       float lr_local, float scale)
+{
+    compressed_pass<kPieceWaves, POW2, WRITE_LOCAL, GT, SPARSE>(tensors, chunks, num_pieces, peers, num_peers, self,
+                                                                t_call, lr_local, scale);
+}
+
+// The count form for more than 16 peers: the decode's arithmetic grows with the workers, and the same
+// squeeze to 6 waves per SIMD pays (VGG-16-shaped list, N = 24 / 32 / 48 / 64: 0.745 / 0.747 / 0.687 / 0.648
+// of peak as the kernel above, 0.779 / 0.777 / 0.732 / 0.705 as this one).
+template <bool WRITE_LOCAL, int GT, bool SPARSE>
+__attribute__((amdgpu_waves_per_eu(6, 6)))
+__global__ __launch_bounds__(64 * kPieceWavesMany) void k_fused_compressed_many(const TensorDesc *__restrict__ tensors,
+                                                                                const ChunkRef *__restrict__ chunks,
+                                                                                unsigned long long num_pieces,
+                                                                                const uint8_t *const *__restrict__ peers,
+                                                                                int num_peers, int self, float t_call,
+                                                                                float lr_local, float scale)
+{
+    compressed_pass<kPieceWavesMany, true, WRITE_LOCAL, GT, SPARSE>(tensors, chunks, num_pieces, peers, num_peers, self,
+                                                                    t_call, lr_local, scale);
 }
 
 // Passes that use the workers' 32-bit gradients (Alg. 1: WARMUP passes and the
