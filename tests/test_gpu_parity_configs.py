@@ -6,8 +6,11 @@ VGG-16, 4 GiB flat bucket) run at full size and are compared on sampled blocks t
 oracle can recompute one by one (first / last / ragged-tail / random blocks; the path is
 elementwise, so a block of outputs depends only on the same block of inputs), plus, over
 the whole buffers, fused == three-call path bit for bit and the conservation property of
-the quantiser.
+the quantiser.  The two layer lists are also compared element by element, whole, for three
+iterations.
 """
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import pytest
 import torch
@@ -57,15 +60,23 @@ def _sample_blocks(cfg, rng, nblocks, blen):
     return out
 
 
+def _partition(cfg, blen):
+    """Every element of every tensor, in blocks of at most blen elements (blen a multiple of 16)."""
+    assert blen % 16 == 0
+    return [(i, a, min(blen, n - a)) for i, n in enumerate(cfg.sizes) for a in range(0, n, blen)]
+
+
 def _run(P, oracle, cfg, dense, steps, blocks, fused=True, self_rank=0, check_peers=True, shadow=False,
-         wl_kwargs=None, max_workgroups=0, static=False):
+         wl_kwargs=None, max_workgroups=0, static=False, threads=1):
     """Steps the workload on the GPU and the oracle on the blocks; compares after every step.
 
     shadow=True keeps a second copy of the observed worker's state that is stepped with the
     three single-tensor calls, and requires whole-arena bit equality with the fused state.
     wl_kwargs: forms of the workload (peers in the sparse form, 16-bit gradients, peers' gradients
     resident so that correction passes sum in the kernel); max_workgroups: bounded grids;
-    static: the pass goes through cdsgd_step_fused_static instead of the plan."""
+    static: the pass goes through cdsgd_step_fused_static instead of the plan.
+    threads: the oracle's blocks are stepped by that many host threads (they are independent: the path is
+    elementwise; the C oracle runs outside the interpreter lock)."""
     pkg, runner, synth = P
     wl = runner.Workload(cfg, dense=dense, self_rank=self_rank, **(wl_kwargs or {}))
     wl.plan.set_max_workgroups(max_workgroups)
@@ -113,9 +124,17 @@ def _run(P, oracle, cfg, dense, steps, blocks, fused=True, self_rank=0, check_pe
                     ok = torch.equal((a[c4::4] - val.to(torch.float32)).view(torch.int32),
                                      wl.residual[c4::4].view(torch.int32))
                     assert ok, "conservation broken at step %d" % s
+        def oracle_step(b):
+            return sims[b].step([np.ascontiguousarray(cap[j][b]) for j in range(N)])
+
+        if threads > 1:
+            with ThreadPoolExecutor(max_workers=threads) as pool:
+                stepped = list(pool.map(oracle_step, range(len(blocks))))
+        else:
+            stepped = [oracle_step(b) for b in range(len(blocks))]
         for b, (i, a, ln) in enumerate(blocks):
-            grads = [np.ascontiguousarray(cap[j][b]) for j in range(N)]
-            c, agg, words = sims[b].step(grads)
+            c, agg, words = stepped[b]
+            stepped[b] = None
             assert c == comp
             tag = "%s step %d block %d (tensor %d, start %d, len %d)" % (cfg.name, s, b, i, a, ln)
             sl = slice(a, a + ln)
@@ -252,3 +271,16 @@ def test_c5_flat_bucket_full_size_other_forms(P, oracle, variant):
         blocks.append((0, int(rng.integers(0, n // 16 - 1024)) * 16, 1 << 14))
     nz, tot = _run(P, oracle, cfg, False, 4, blocks, **VARIANTS[variant])
     assert 0.05 * tot < nz < 0.25 * tot
+
+
+@pytest.mark.parametrize("name", ["c3_resnet50", "c4_vgg16"])
+def test_whole_list_every_element(P, oracle, name):
+    """The ResNet-50- and VGG-16-shaped lists at full size with EVERY element compared with the oracle (not
+    sampled blocks): one correction pass and two compressed ones, dense recipe, the oracle stepped by 16
+    host threads over 4 Mi-element blocks.  (The played peers' streams are checked on samples by the tests
+    above; here only the observed worker's outputs are downloaded.)"""
+    cfg = P[2].config(name)
+    blocks = _partition(cfg, 1 << 22)
+    assert sum(ln for _, _, ln in blocks) == cfg.elements
+    nz, tot = _run(P, oracle, cfg, True, 3, blocks, check_peers=False, threads=16)
+    assert tot == 2 * cfg.elements and nz > 0.2 * tot
