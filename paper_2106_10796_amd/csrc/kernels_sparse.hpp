@@ -70,25 +70,28 @@ __global__ __launch_bounds__(256) void k_sparse_encode(const uint32_t *__restric
     if (i == 0 && seg_words) seg_words[blockIdx.x] = 8u + total;
 }
 
-// a4 on sparse streams, one tensor: 512 lanes per chunk, lane tid takes quads tid and 512 + tid, the
-// workers' bytes staged through LDS sixteen workers at a time as in k_decode_sum.  Per batch the 16 x 8
-// bitmap words go to LDS first (one word per lane); then wave w rebuilds the chunk's 256 packed words of
-// workers w and w + 8, four consecutive words per lane with one 128-bit load of the non-zero ones among
-// them; then every lane picks its two bytes of each worker.
-template <bool POW2>
-__global__ __launch_bounds__(512) void k_decode_sum_sparse(StreamTable tab, int num_workers,
-                                                           float *__restrict__ agg_out, Extent ext, float t,
-                                                           float bias_t)
+// a4 on sparse streams, one tensor: LANES lanes per chunk as in k_decode_sum (lane tid takes quads tid,
+// LANES + tid, ...), the workers' bytes staged through LDS sixteen workers at a time.  Per batch the 16 x 8
+// bitmap words go to LDS first (one word per lane); then every wave rebuilds the chunk's 256 packed words
+// of its share of the workers, four consecutive words per lane with one 128-bit load of the non-zero ones
+// among them; then every lane picks its bytes of each worker.
+template <bool POW2, unsigned LANES>
+__global__ __launch_bounds__(LANES) void k_decode_sum_sparse(StreamTable tab, int num_workers,
+                                                             float *__restrict__ agg_out, Extent ext, float t,
+                                                             float bias_t)
 {
+    constexpr unsigned Q = kChunkQuads / LANES, kWaves = LANES / 64u;
+    static_assert(kChunkQuads == 1024 && (LANES == 256 || LANES == 512), "four packed words per lane cover a worker's chunk");
     __shared__ __attribute__((aligned(16))) uint8_t rows[16][kChunkQuads];
     __shared__ uint32_t bitmaps[16][8];
-    static_assert(kChunkQuads == 1024 && kBlock == 512 && kQpl == 2, "four packed words per lane cover a worker's chunk");
     const unsigned tid = threadIdx.x, lane = tid & 63u;
     const int wave = __builtin_amdgcn_readfirstlane((int)(tid >> 6));
     const unsigned chunk = blockIdx.x;
     const bool tail = chunk >= ext.full_chunks;
     const unsigned rem_elems = tail ? ext.tail_elems : kChunkElems;
-    f4 agg[kQpl] = {f4{0.0f, 0.0f, 0.0f, 0.0f}, f4{0.0f, 0.0f, 0.0f, 0.0f}};
+    f4 agg[Q];
+#pragma unroll
+    for (unsigned j = 0; j < Q; ++j) agg[j] = f4{0.0f, 0.0f, 0.0f, 0.0f};
     unsigned acc[4] = {0u, 0u, 0u, 0u};
     for (int p0 = 0; p0 < num_workers; p0 += 16) {
         const int np = num_workers - p0 < 16 ? num_workers - p0 : 16;
@@ -100,8 +103,8 @@ __global__ __launch_bounds__(512) void k_decode_sum_sparse(StreamTable tab, int 
         }
         __syncthreads();
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int k = wave + 8 * h;
+        for (int h = 0; h < (int)(16 / kWaves); ++h) {
+            const int k = wave + (int)kWaves * h;
             if (k < np) {
                 const uint32_t *seg = reinterpret_cast<const uint32_t *>(tab.p[p0 + k]) + (size_t)chunk * kSegStride;
                 // (pad words past the end of the stream have no bit set: a ragged chunk needs no other care)
@@ -110,17 +113,19 @@ __global__ __launch_bounds__(512) void k_decode_sum_sparse(StreamTable tab, int 
         }
         __syncthreads();
         for (int k = 0; k < np; ++k) {
-            const unsigned w = (unsigned)rows[k][tid] | ((unsigned)rows[k][512u + tid] << 8);
+            unsigned w = 0;
+#pragma unroll
+            for (unsigned j = 0; j < Q; ++j) w |= (unsigned)rows[k][j * LANES + tid] << (8u * j);
             if (POW2) count_codes(acc, w);
-            else chain_codes(agg, w, t);
+            else chain_codes<Q>(agg, w, t);
         }
         __syncthreads();
     }
-    if (POW2) counts_to_sum(agg, acc, t, bias_t);
+    if (POW2) counts_to_sum<Q>(agg, acc, t, bias_t);
     float *out = agg_out + (size_t)chunk * kChunkElems;
 #pragma unroll
-    for (unsigned j = 0; j < kQpl; ++j) {
-        const unsigned qi = j * kBlock + tid;
+    for (unsigned j = 0; j < Q; ++j) {
+        const unsigned qi = j * LANES + tid;
         if (!tail) st4(out, qi, agg[j]);
         else st4g<true>(out, qi, quad_count<true>(rem_elems, qi), agg[j]);
     }

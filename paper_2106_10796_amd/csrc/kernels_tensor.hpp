@@ -6,8 +6,7 @@ namespace {
 // ---------------------------------------------------------------------------
 // a4: decode-and-sum (Sec. 3.2.1; sum of eq. 10)
 // ---------------------------------------------------------------------------
-// A lane keeps the packed bytes of its kQpl quads of one worker in one
-// register: byte j = quad j.
+// A lane keeps the packed bytes of its Q quads of one worker in one register: byte j = quad j.
 
 typedef unsigned u4 __attribute__((ext_vector_type(4)));
 
@@ -19,15 +18,16 @@ __device__ __forceinline__ unsigned signed_fields(unsigned w)
     return (x ^ y) | ((y & ~x) << 1);
 }
 
-// Literal fp32 chain: agg += value(code) for the 4*kQpl elements of this lane,
+// Literal fp32 chain: agg += value(code) for the 4 Q elements of this lane (Q quads, Q <= 4),
 // one rounded add per element.  The codes are first rewritten, 16 at a time,
 // as 2-bit two's-complement fields so that one signed bit-field extract
 // yields the multiplier.
-__device__ __forceinline__ void chain_codes(f4 (&agg)[kQpl], unsigned w, float t)
+template <unsigned Q>
+__device__ __forceinline__ void chain_codes(f4 (&agg)[Q], unsigned w, float t)
 {
     const unsigned s = signed_fields(w);
 #pragma unroll
-    for (unsigned j = 0; j < kQpl; ++j) {
+    for (unsigned j = 0; j < Q; ++j) {
 #pragma unroll
         for (unsigned c = 0; c < 4; ++c) {
             const int m = ((int)(s << (30u - (8u * j + 2u * c)))) >> 30;
@@ -51,11 +51,11 @@ __device__ __forceinline__ void count_codes(unsigned (&acc)[4], unsigned w)
 }
 
 // acc holds 2*num_summed + sum of values; bias_t = -(2*num_summed)*t.
-__device__ __forceinline__ void counts_to_sum(f4 (&agg)[kQpl], const unsigned (&acc)[4], float t,
-                                              float bias_t)
+template <unsigned Q>
+__device__ __forceinline__ void counts_to_sum(f4 (&agg)[Q], const unsigned (&acc)[4], float t, float bias_t)
 {
 #pragma unroll
-    for (unsigned j = 0; j < kQpl; ++j) {
+    for (unsigned j = 0; j < Q; ++j) {
 #pragma unroll
         for (unsigned c = 0; c < 4; ++c) {
             const float cnt = (float)((acc[c] >> (8u * j)) & 0xFFu);
@@ -69,18 +69,19 @@ struct StreamTable {
     const uint8_t *p[CDSGD_MAX_WORKERS];
 };
 
-// a4 for one tensor: 512 lanes per chunk, the workers' bytes staged through LDS.  Sixteen workers at
-// a time, wave w fetches the chunk's 1 KiB of workers w and w + 8 of the batch with one 128-bit load per
-// lane (a wave-uniform worker, so its pointer is a scalar load from the kernel arguments), the bytes go
-// to LDS as [worker][byte], and every lane then reads its two bytes (quads tid and 512 + tid) of each
-// worker back (measured on 2^27 elements, N = 16, count form: 6.17 TB/s, against 5.6-5.8 TB/s with a
-// byte-wide global load per worker and lane, four workers in flight at a time).
-template <bool POW2>
-__global__ __launch_bounds__(512) void k_decode_sum(StreamTable tab, int num_workers, float *__restrict__ agg_out,
-                                                    Extent ext, float t, float bias_t)
+// a4 for one tensor: LANES lanes per chunk (Q = 1024 / LANES quads per lane: quads tid, LANES + tid, ...),
+// the workers' bytes staged through LDS.  Sixteen workers at a time, every wave fetches the chunk's 1 KiB
+// of its share of them with one 128-bit load per lane and worker (a wave-uniform worker, so its pointer
+// is a scalar load from the kernel arguments), the bytes go to LDS as [worker][byte], and every lane then
+// reads its Q bytes of each worker back (measured on 2^27 elements, N = 16, count form, 512 lanes:
+// 6.17 TB/s, against 5.6-5.8 TB/s with a byte-wide global load per worker and lane).
+template <bool POW2, unsigned LANES>
+__global__ __launch_bounds__(LANES) void k_decode_sum(StreamTable tab, int num_workers, float *__restrict__ agg_out,
+                                                      Extent ext, float t, float bias_t)
 {
+    constexpr unsigned Q = kChunkQuads / LANES, kWaves = LANES / 64u;
+    static_assert(kChunkQuads == 1024 && (LANES == 256 || LANES == 512), "one 128-bit load per lane covers a worker's chunk");
     __shared__ __attribute__((aligned(16))) uint8_t rows[16][kChunkQuads];
-    static_assert(kChunkQuads == 1024 && kBlock == 512 && kQpl == 2, "one 128-bit load per lane covers a worker's chunk");
     const unsigned tid = threadIdx.x, lane = tid & 63u;
     const int wave = __builtin_amdgcn_readfirstlane((int)(tid >> 6));
     const unsigned chunk = blockIdx.x;
@@ -88,15 +89,17 @@ __global__ __launch_bounds__(512) void k_decode_sum(StreamTable tab, int num_wor
     const bool tail = chunk >= ext.full_chunks;
     const unsigned rem_elems = tail ? ext.tail_elems : kChunkElems;
     const unsigned rem_bytes = tail ? ext.tail_bytes : kChunkQuads;
-    f4 agg[kQpl] = {f4{0.0f, 0.0f, 0.0f, 0.0f}, f4{0.0f, 0.0f, 0.0f, 0.0f}};
+    f4 agg[Q];
+#pragma unroll
+    for (unsigned j = 0; j < Q; ++j) agg[j] = f4{0.0f, 0.0f, 0.0f, 0.0f};
     unsigned acc[4] = {0u, 0u, 0u, 0u};
     for (int p0 = 0; p0 < num_workers; p0 += 16) {
         const int np = num_workers - p0 < 16 ? num_workers - p0 : 16;
-        u4 cw[2];
+        u4 cw[16 / kWaves];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int h = 0; h < (int)(16 / kWaves); ++h) {
             cw[h] = u4{0u, 0u, 0u, 0u};
-            const int k = wave + 8 * h;
+            const int k = wave + (int)kWaves * h;
             if (k < np) {
                 const uint8_t *src = tab.p[p0 + k] + quad0 + 16u * lane;
                 if (16u * lane + 16u <= rem_bytes) {
@@ -111,21 +114,23 @@ __global__ __launch_bounds__(512) void k_decode_sum(StreamTable tab, int num_wor
             }
         }
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
-            if (wave + 8 * h < np) *reinterpret_cast<u4 *>(&rows[wave + 8 * h][16u * lane]) = cw[h];
+        for (int h = 0; h < (int)(16 / kWaves); ++h)
+            if (wave + (int)kWaves * h < np) *reinterpret_cast<u4 *>(&rows[wave + (int)kWaves * h][16u * lane]) = cw[h];
         __syncthreads();
         for (int k = 0; k < np; ++k) {
-            const unsigned w = (unsigned)rows[k][tid] | ((unsigned)rows[k][512u + tid] << 8);
+            unsigned w = 0;
+#pragma unroll
+            for (unsigned j = 0; j < Q; ++j) w |= (unsigned)rows[k][j * LANES + tid] << (8u * j);
             if (POW2) count_codes(acc, w);
-            else chain_codes(agg, w, t);
+            else chain_codes<Q>(agg, w, t);
         }
         __syncthreads();
     }
-    if (POW2) counts_to_sum(agg, acc, t, bias_t);
+    if (POW2) counts_to_sum<Q>(agg, acc, t, bias_t);
     float *out = agg_out + 4 * quad0;
 #pragma unroll
-    for (unsigned j = 0; j < kQpl; ++j) {
-        const unsigned qi = j * kBlock + tid;
+    for (unsigned j = 0; j < Q; ++j) {
+        const unsigned qi = j * LANES + tid;
         if (!tail) st4(out, qi, agg[j]);
         else st4g<true>(out, qi, quad_count<true>(rem_elems, qi), agg[j]);
     }
