@@ -7,7 +7,7 @@ oracle can recompute one by one (first / last / ragged-tail / random blocks; the
 elementwise, so a block of outputs depends only on the same block of inputs), plus, over
 the whole buffers, fused == three-call path bit for bit and the conservation property of
 the quantiser.  The two layer lists are also compared element by element, whole, for three
-iterations.
+iterations, and the 4 GiB bucket for its first two.
 """
 from concurrent.futures import ThreadPoolExecutor
 
@@ -284,3 +284,49 @@ def test_whole_list_every_element(P, oracle, name):
     assert sum(ln for _, _, ln in blocks) == cfg.elements
     nz, tot = _run(P, oracle, cfg, True, 3, blocks, check_peers=False, threads=16)
     assert tot == 2 * cfg.elements and nz > 0.2 * tot
+
+
+def test_c5_flat_bucket_every_element(P, oracle):
+    """The 4 GiB bucket with EVERY one of its 2^30 elements compared with the oracle, for the first two
+    iterations: a correction pass, then a compressed pass (the residuals are still zero when it starts, so
+    no earlier iteration's state is needed on the host).  All 16 workers' gradients stay resident on the
+    GPU; after each pass the buffer is walked in blocks of 4 Mi elements: the workers' gradients of the
+    block come down, 16 host threads step the oracle from the weights the pass started with, and the
+    block's packed words, residual and both weights are compared bit for bit."""
+    pkg, runner, synth = P
+    cfg = synth.config("c5_flat4g")
+    n, N, t = cfg.sizes[0], cfg.num_workers, cfg.threshold
+    wl = runner.Workload(cfg, full_grads=True)
+    blen = 1 << 22
+    starts = list(range(0, n, blen))
+    assert len(starts) * blen == n
+    for it in (0, 1):
+        w_before = wl.w_global.clone()
+        wl.prepare_step(it)
+        assert wl.compressed(it) == (it == 1)
+        wl.fused_step(it)                    # the correction pass sums the 16 resident gradients in the kernel
+        torch.cuda.synchronize()
+
+        def check(a, it=it, w_before=w_before):
+            sl, wsl = slice(a, a + blen), slice(a // 16, (a + blen) // 16)
+            grads = [(wl.grad if j == 0 else wl.peer_grad[j])[sl].cpu().numpy() for j in range(N)]
+            sim = oracle.Simulation(w_before[sl].cpu().numpy(), N, cfg.k, t, cfg.lr, cfg.lr, 0)
+            sim.count = it                   # the loop's counter before this pass; residuals are zero either way
+            comp, agg, words = sim.step(grads)
+            assert comp == (it == 1)
+            tag = "iteration %d, block at %d" % (it, a)
+            fired = 0
+            if comp:
+                assert_bits_equal(wl.packed_self[wsl].cpu().numpy(), words[0].view(np.int32), "packed_self " + tag)
+                fired = int((oracle.unpack(words[0], blen) != 0).sum())
+            assert_bits_equal(wl.residual[sl].cpu().numpy(), sim.residual[0], "residual " + tag)
+            assert_bits_equal(wl.w_global[sl].cpu().numpy(), sim.w_global, "w_global " + tag)
+            assert_bits_equal(wl.w_local[sl].cpu().numpy(), sim.w_local, "w_local " + tag)
+            return fired
+
+        with ThreadPoolExecutor(max_workers=16) as pool:
+            fired = sum(pool.map(check, starts))
+        if it == 1:
+            assert 0.05 * n < fired < 0.15 * n   # exp(-2.5) = 8.2 % of the codes fire on the first compressed pass
+        del w_before
+    wl.destroy()
