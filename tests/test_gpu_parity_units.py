@@ -161,7 +161,8 @@ def test_probe_streams_moves_what_it_says(B):
 
 def _run_layer_list(B, oracle, sizes, N, self_rank, k, t, steps, seed, lr_l=0.4, lr_g=0.1, stepper=None):
     """Fused step vs oracle vs the three-call composition on an arbitrary layer list.
-    stepper(plan, s): how iteration s is enqueued (default: one cdsgd_step_fused over the list)."""
+    stepper(plan, s): how iteration s is enqueued (default: one cdsgd_step_fused over the list); the plan
+    carries what a stepper may need beyond it as attributes (layer_list, peer_rows)."""
     rng = np.random.default_rng(seed)
     T = len(sizes)
     dev = dict(device="cuda")
@@ -181,6 +182,7 @@ def _run_layer_list(B, oracle, sizes, N, self_rank, k, t, steps, seed, lr_l=0.4,
     peers = [None if j == self_rank else [B.new_packed(n) for n in sizes] for j in range(N)]
     tensors = [{key: state[0][key][i] for key in state[0]} for i in range(T)]
     plan = B.Plan(tensors, peers if N > 1 else None, N, self_rank)
+    plan.layer_list, plan.peer_rows = tensors, (peers if N > 1 else None)
     sims = [oracle.Simulation(W0[i], N, k, t, lr_l, lr_g, self_rank) for i in range(T)]
     agg_dev = [torch.zeros(n, dtype=torch.float32, **dev) for n in sizes]
     for s in range(steps):
@@ -397,7 +399,8 @@ def test_fused_step_many_tiny_tensors(B, oracle):
 def test_fused_step_random_configurations(B, oracle):
     """Seeded random layer lists, worker counts, positions, periods and thresholds (both decode
     forms), each checked step by step against the oracle and the three-call composition; every
-    third case steps the list as ranges of tensors in a random order.
+    third case steps the list as ranges of tensors in a random order, every third through
+    cdsgd_step_fused_static.
     CDSGD_FUZZ_CASES raises the number of cases for a longer soak."""
     import os
     cases = int(os.environ.get("CDSGD_FUZZ_CASES", "40"))
@@ -430,6 +433,10 @@ def test_fused_step_random_configurations(B, oracle):
             def stepper(plan, s, groups=groups, k=k, t=t):
                 for lo, cnt in groups:
                     plan.step_range(lo, cnt, s, k, t, 0.4, 0.1)
+        elif case % 3 == 1:
+            # ... and every third one goes through the entry point that allocates nothing
+            def stepper(plan, s, N=N, self_rank=self_rank, k=k, t=t):
+                B.cdsgd_step_fused_static(plan.layer_list, plan.peer_rows, N, self_rank, s, k, t, 0.4, 0.1)
         try:
             _run_layer_list(B, oracle, sizes, N, self_rank, k=k, t=t, steps=int(rng.integers(2, 5)),
                             seed=9000 + case, stepper=stepper)
