@@ -69,7 +69,11 @@ namespace {
 //   update, both rules              6.36 / 6.34 / - / 6.55 / - / 6.50 / 6.55 / 6.18
 //   correction pass, sum in kernel  6.19 / 6.39-6.41 / 6.35 / 6.24 / - / 5.97
 // eq. 11 alone and the compressed pass (whose workgroups already hold 4-16 KiB of staged codes) lose with
-// any bound and get none.
+// any bound and get none.  The same bound stated to the compiler instead (amdgpu_waves_per_eu with a maximum of
+// 5) gives 6.55 and 6.45 TB/s on the first and the third line: most of the gain, not all of it.  While a
+// pass launched this way runs it holds the compute units' LDS, so a kernel of another stream that needs
+// LDS waits for it; a pass with a workgroup limit (cdsgd_plan_set_max_workgroups), which is meant to run
+// beside other kernels, is launched without the bound.
 constexpr unsigned kLdsFor20Waves = 8192;
 constexpr unsigned kLdsFor26Waves = 6144;
 
@@ -291,8 +295,11 @@ int launch_full_pass(const PlanTables *plan, int local_mode, float lr_local, flo
     const unsigned long long num_pieces = (unsigned long long)plan->num_chunks * kPiecesPerChunk;
     const dim3 grid(plan->grid_size(num_pieces, kFullBlock)), block(kFullBlock);
     const int np = plan->num_workers - 1;
+    // a pass with a workgroup limit is meant to share the GPU with other kernels: it leaves the LDS to them
+    const unsigned lds_plain = plan->max_workgroups ? 0u : kLdsFor20Waves;
+    const unsigned lds_sum = plan->max_workgroups ? 0u : kLdsFor26Waves;
 #define CDSGD_LAUNCH_FULL_T(SUM, LOCAL, GT)                                                                    \
-    hipLaunchKernelGGL((k_fused_full<SUM, LOCAL, GT>), grid, block, (SUM ? kLdsFor26Waves : kLdsFor20Waves), s,  \
+    hipLaunchKernelGGL((k_fused_full<SUM, LOCAL, GT>), grid, block, (SUM ? lds_sum : lds_plain), s,              \
                        plan->tensors, plan->chunk_table(),                                                      \
                        num_pieces, plan->peer_grads, np, plan->self, lr_local, scale)
 #define CDSGD_LAUNCH_FULL(SUM, LOCAL)                                                                          \
